@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the Dense-and-Sparse LUT matvec on one MI355X.
+
+Workload (default): the LLaMA-7B-shaped MLP pair at 3 bits — layers 11008x4096 and 4096x11008, 8 fp16
+centroids per output row, 0.45 % fp16 CSR outliers with row-skewed counts (10 % of the rows hold 50 % of the
+nonzeros), batch 1, synthetic seeded weights (Student-t(4) * 0.02) and N(0,1) activations.
+
+A "step" is one pass of the hot path over that pair: two calls of sqllm_dense_sparse_matvec, back to back on
+one stream.  To measure HBM and not the 256 MB last-level cache, the steps rotate over enough copies of the
+two layers (at distinct addresses) for the working set to exceed 1 GB.  All inputs are resident in HBM
+before the timed region starts.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+SEED = 20230613
+WORKLOADS = {
+    # name: (list of (M, N), bits, frac, skew, B)
+    "llama7b_mlp_pair_3bit": ([(11008, 4096), (4096, 11008)], 3, 0.0045, (0.10, 0.50), 1),
+    "llama7b_mlp_pair_4bit": ([(11008, 4096), (4096, 11008)], 4, 0.0045, (0.10, 0.50), 1),
+    "single_4096_4bit": ([(4096, 4096)], 4, 0.0045, None, 1),
+    "llama13b_mlp_pair_3bit": ([(13824, 5120), (5120, 13824)], 3, 0.0045, (0.10, 0.50), 1),
+    "llama65b_mlp_pair_3bit": ([(22016, 8192), (8192, 22016)], 3, 0.0045, (0.01, 0.30), 1),
+}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="llama7b_mlp_pair_3bit", choices=sorted(WORKLOADS))
+    ap.add_argument("--footprint-gb", type=float, default=1.1, help="bytes of distinct weight copies to rotate over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rows-per-wg", type=int, default=0)
+    return ap.parse_args()
+
+
+def time_steps(torch, fn, steps, warmup):
+    """K calls of fn(step) bracketed by device synchronisation; HIP events on the launch stream."""
+    for s in range(warmup):
+        fn(s)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for s in range(steps):
+        fn(warmup + s)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return e0.elapsed_time(e1) * 1e-3, wall
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the path is a single-GPU matvec); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import gen
+    import paper_2306_07629_amd as sq
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    shapes, bits, frac, skew, B = WORKLOADS[args.workload]
+    if args.rows_per_wg:
+        sq.sqllm_set_rows_per_workgroup(args.rows_per_wg)
+
+    # ---- generate, upload, check parity against the oracle before any timing
+    import oracle  # only for the parity gate and the cpu_baseline leg
+    layers, dev, worst = [], [], 0.0
+    for li, (M, N) in enumerate(shapes):
+        L = gen.make_layer(M, N, bits, frac=frac, skew=skew, B=B, seed=gen.layer_seed(SEED, 2, li))
+        D = sq.DeviceLayer(L)
+        y = D.matvec().cpu().numpy().view(np.float16).astype(np.float64)
+        y_ref, absdot = oracle.layer_matvec(L)
+        ratio = float(np.max(np.abs(y - y_ref) / (2e-3 * absdot)))
+        if not (ratio <= 1.0):
+            print(f"bench.py: parity FAILED for layer {M}x{N}: worst err/bound {ratio}", file=sys.stderr)
+            sys.exit(4)
+        worst = max(worst, ratio)
+        layers.append(L); dev.append(D)
+
+    alg_bytes = [sq.sqllm_algorithmic_bytes(L.M, L.N, L.bits, L.nnz, L.B) for L in layers]
+    step_bytes = sum(alg_bytes)
+    copies = max(2, int(np.ceil(args.footprint_gb * 1e9 / step_bytes)))
+    ring = [[D] + [D.clone_weights() for _ in range(copies - 1)] for D in dev]
+    torch.cuda.synchronize()
+
+    def step_cold(s):
+        c = s % copies
+        for r in ring:
+            r[c].matvec()
+
+    def step_warm(s):
+        for D in dev:
+            D.matvec()
+
+    sec_cold, wall_cold = time_steps(torch, step_cold, args.steps, args.warmup)
+    sec_warm, _ = time_steps(torch, step_warm, args.steps, args.warmup)
+    launches = args.steps * len(shapes)
+    us_per_matvec = sec_cold / launches * 1e6
+    gbs = step_bytes * args.steps / sec_cold / 1e9
+
+    # ---- fp16 baselines on the same shapes (own kernel and the vendor library through torch), cold as well
+    fp16_bytes = sum(M * N * 2 + (M + N) * 2 for M, N in shapes)
+    fcopies = max(2, int(np.ceil(args.footprint_gb * 1e9 / fp16_bytes)))
+    wring = [[(torch.randn(M, N, device="cuda", dtype=torch.float16) * 0.02) for _ in range(fcopies)] for M, N in shapes]
+    xs = [torch.randn(N, device="cuda", dtype=torch.float16) for M, N in shapes]
+    ys = [torch.zeros(M, device="cuda", dtype=torch.float16) for M, N in shapes]
+
+    def step_fp16_own(s):
+        c = s % fcopies
+        for k, (M, N) in enumerate(shapes):
+            sq.sqllm_fp16_gemv(M, N, 1, wring[k][c], xs[k], ys[k])
+
+    def step_fp16_torch(s):
+        c = s % fcopies
+        for k in range(len(shapes)):
+            torch.mv(wring[k][c], xs[k], out=ys[k])
+
+    fsteps = max(20, args.steps // 4)
+    sec_f_own, _ = time_steps(torch, step_fp16_own, fsteps, 10)
+    sec_f_torch, _ = time_steps(torch, step_fp16_torch, fsteps, 10)
+    us_f_own = sec_f_own / (fsteps * len(shapes)) * 1e6
+    us_f_torch = sec_f_torch / (fsteps * len(shapes)) * 1e6
+    us_f = min(us_f_own, us_f_torch)
+    del wring
+
+    # ---- HBM traffic per launch measured with rocprofv3 counters, if a summary is committed
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_" + args.workload + ".json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    # ---- CPU baseline: the oracle as it stands, on this machine's host cores, bounded sample
+    cpu = None
+    if not args.no_cpu_baseline:
+        times = []
+        t_begin = time.perf_counter()
+        reps = 0
+        while reps < 3 or (time.perf_counter() - t_begin < 10.0 and reps < 12):
+            t0 = time.perf_counter()
+            for L in layers:
+                oracle.layer_matvec(L)
+            times.append(time.perf_counter() - t0)
+            reps += 1
+        med = sorted(times)[len(times) // 2]
+        cpu = {"value": med / len(shapes) * 1e6, "unit": "us per matvec", "cores": oracle.threads(), "kind": "oracle",
+               "sample": f"{reps} full passes over the same {len(shapes)} layers (median), fp64, OpenMP over rows",
+               "gbs": step_bytes / med / 1e9}
+
+    out = {
+        "metric": "us per dense+sparse matvec (3-bit LUT + 0.45% CSR), effective HBM GB/s in roofline" if bits == 3
+                  else "us per dense+sparse matvec (4-bit LUT + 0.45% CSR), effective HBM GB/s in roofline",
+        "value": us_per_matvec, "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec_cold / args.steps * 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
+        "config": {"workload": args.workload, "layers": [f"{M}x{N}" for M, N in shapes], "bits": bits, "sparse_frac": frac,
+                   "skew": skew, "batch": B, "seed": SEED, "weight_copies_rotated": copies,
+                   "working_set_gb": step_bytes * copies / 1e9, "matvecs_per_step": len(shapes)},
+        "effective_gbs": gbs, "pct_of_hbm_roofline": 100.0 * gbs / HBM_PEAK_GBS,
+        "warm_us_per_matvec": sec_warm / launches * 1e6, "warm_effective_gbs": step_bytes * args.steps / sec_warm / 1e9,
+        "fp16_gemv_us": {"own_kernel": us_f_own, "torch_mv": us_f_torch}, "speedup_vs_fp16": us_f / us_per_matvec,
+        "parity_worst_err_over_bound": worst, "host_wall_s_timed_region": wall_cold,
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                     "traffic": traffic, "kernel": f"sqllm::matvec_kernel<{bits},1,*>",
+                     "algorithmic_bytes_per_launch": step_bytes / len(shapes)},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

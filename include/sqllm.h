@@ -1,0 +1,117 @@
+/*
+ * sqllm.h — C ABI of the Dense-and-Sparse look-up-table matvec for AMD MI355X (gfx950).
+ *
+ * The library computes, for one linear layer and a small batch of activation vectors,
+ *
+ *        Y = D X + S X                                   (paper Sec. 4.2: W = D + S, W X = D X + S X)
+ *
+ *   D  (M x N)  dense part, stored as b-bit indices (b = 3 or 4) into ONE look-up table of 2^b fp16
+ *               values PER OUTPUT ROW:  D[i][j] = lut[i][ idx(i,j) ]
+ *               (Sec. 4.3 "the compressed matrices store 3/4-bit indices, which correspond to LUT entries
+ *               containing FP16 values"; Sec. 5 "each output channel is assigned a separate lookup table").
+ *   S  (M x N)  sparse part in compressed-sparse-row form with fp16 values (Sec. 4.2: outliers and
+ *               sensitive values kept in FP16 and stored in CSR).
+ *   X  (N x B)  fp16 activations, B = 1..8 vectors;  Y (M x B) fp16.
+ *
+ * STORAGE FORMAT (the paper does not fix one; this is the contract of this library)
+ *   qidx   row i is a little-endian bit stream of N*b bits starting at byte i*N*b/8.  Element j owns stream
+ *          bits [j*b, j*b+b), least-significant bit first; stream bit k is bit (k mod 8) of byte (k div 8).
+ *          Rows follow each other without padding.  N must be a multiple of 128, so a row is a whole number
+ *          of 48-byte (b=3) or 64-byte (b=4) groups of 128 elements.
+ *   lut    fp16 [M][2^b], row-major.  No ordering of the entries is assumed.
+ *   rowptr int32 [M+1], rowptr[0] = 0, non-decreasing, rowptr[M] = nnz.
+ *   cols   int32 [nnz], 0 <= cols[p] < N.   vals  fp16 [nnz].  Duplicate (row, col) entries add up.
+ *   x      fp16 [N][B] row-major (x[j*B + t]);   y  fp16 [M][B] row-major.
+ *
+ * ARITHMETIC  table look-ups are exact selections; products of fp16 values are accumulated in fp32; each
+ *   y element is rounded to fp16 once.  The order of the fp32 additions is fixed for a given shape and
+ *   launch configuration (no floating-point atomics are used), so results are reproducible run to run.
+ *
+ * OWNERSHIP / EXECUTION  every pointer is a caller-owned DEVICE pointer (unless stated otherwise) that must
+ *   stay valid until the work enqueued on `stream` has finished.  The library never allocates, frees or
+ *   synchronises: each call validates its arguments on the host, enqueues kernels on `stream`
+ *   (a hipStream_t passed as void*, NULL = the default stream) and returns.  Device-side data (index
+ *   ranges of cols, monotonicity of rowptr) is NOT validated; out-of-range columns are undefined behaviour.
+ *
+ * ERRORS  every function returns an sqllm_status; nothing is enqueued unless SQLLM_OK is returned.  A text
+ *   for the last error of the calling thread is available from sqllm_last_error_string().
+ *   M == 0 or B*M == 0 -> SQLLM_OK, nothing enqueued.
+ *
+ * ALIGNMENT  qidx and x must be 16-byte aligned; lut 16-byte; y, vals 2-byte; rowptr, cols 4-byte.
+ */
+#ifndef SQLLM_H
+#define SQLLM_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SQLLM_OK = 0,
+    SQLLM_ERR_NULL = 1,   /* a required pointer is NULL                                   */
+    SQLLM_ERR_BITS = 2,   /* bits is not 3 or 4                                           */
+    SQLLM_ERR_SHAPE = 3,  /* M < 0, N <= 0, N % 128 != 0, or N > SQLLM_MAX_N              */
+    SQLLM_ERR_ALIGN = 4,  /* a pointer violates the alignment rules above                 */
+    SQLLM_ERR_NNZ = 5,    /* nnz < 0 or nnz >= 2^31                                       */
+    SQLLM_ERR_BATCH = 6,  /* B outside 1..SQLLM_MAX_BATCH                                 */
+    SQLLM_ERR_HIP = 7,    /* the HIP runtime reported an error (see the error string)     */
+    SQLLM_ERR_DEVICE = 8  /* the current device is not a gfx950 GPU                       */
+} sqllm_status;
+
+#define SQLLM_MAX_BATCH 8
+#define SQLLM_MAX_N 32768 /* widest row a workgroup covers with one 2048-column slice per wave */
+
+/* Dense term only (Sec. 4.3, the LUT-based matrix-vector kernel):
+ *   accumulate == 0:  y = D x          accumulate != 0:  y = fp16( fp32(y) + D x )                        */
+int sqllm_lut_gemv(int M, int N, int bits, int B,
+                   const void* qidx, const void* lut, const void* x, void* y,
+                   int accumulate, void* stream);
+
+/* Sparse term only (Sec. 4.3, the balanced CSR kernel: every thread of a workgroup takes the same number
+ * of nonzeros regardless of which row they fall in, and rows shared by several threads are combined on
+ * chip):   accumulate == 0:  y = S x        accumulate != 0:  y = fp16( fp32(y) + S x )
+ * nnz == 0 is allowed (cols/vals may then be NULL; rowptr is not read).                                  */
+int sqllm_csr_spmv(int M, int N, long long nnz, int B,
+                   const int* rowptr, const int* cols, const void* vals,
+                   const void* x, void* y, int accumulate, void* stream);
+
+/* Both terms in ONE kernel launch (Sec. 4.3: dense and sparse kernels are launched in one call so that no
+ * separate pass sums their outputs):  y = fp16( D x + S x ), summed in fp32.  nnz == 0 -> dense only.    */
+int sqllm_dense_sparse_matvec(int M, int N, int bits, long long nnz, int B,
+                              const void* qidx, const void* lut,
+                              const int* rowptr, const int* cols, const void* vals,
+                              const void* x, void* y, void* stream);
+
+/* One thread per row over the CSR matrix — the "standard" kernel the paper's App. C compares the balanced
+ * one against.  Same arguments and result as sqllm_csr_spmv; kept as the ablation baseline.              */
+int sqllm_csr_spmv_rowwise(int M, int N, long long nnz, int B,
+                           const int* rowptr, const int* cols, const void* vals,
+                           const void* x, void* y, int accumulate, void* stream);
+
+/* Parity exports: the same in-register decode as the matvec kernels, written out.
+ *   idx_out  uint8 [M][N]  index of every element (Sec. 4.3, b-bit indices)
+ *   w_out    fp16  [M][N]  lut[i][idx(i,j)]        (Sec. 4.3, dequantisation by table look-up)           */
+int sqllm_unpack_indices(int M, int N, int bits, const void* qidx, void* idx_out, void* stream);
+int sqllm_dequantize(int M, int N, int bits, const void* qidx, const void* lut, void* w_out, void* stream);
+
+/* fp16 baseline the paper measures its speed-ups against (Tab. 3, FP16 row): y = W x with
+ * W fp16 [M][N] row-major, fp32 accumulation, fp16 result.  N % 8 == 0, w and x 16-byte aligned.         */
+int sqllm_fp16_gemv(int M, int N, int B, const void* w, const void* x, void* y, void* stream);
+
+/* Bytes the method moves for one matvec (indices + tables + CSR arrays + x + y); used for GB/s figures.  */
+long long sqllm_algorithmic_bytes(int M, int N, int bits, long long nnz, int B);
+
+/* Tuning knob: rows handled by one workgroup of the matvec kernels (0 = library default).  Affects speed
+ * and the fp32 summation grouping only.  Returns the previous value.  Process-wide, not thread-safe.     */
+int sqllm_set_rows_per_workgroup(int rows);
+
+const char* sqllm_last_error_string(void); /* host pointer, valid until the thread's next failing call */
+const char* sqllm_status_string(int status);
+int sqllm_version(void);                   /* major*10000 + minor*100 + patch */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SQLLM_H */

@@ -1,0 +1,117 @@
+"""ctypes binding of the C ABI in include/sqllm.h.  Argument marshalling only: every step of the matvec
+runs in the HIP kernels of libsqllm.so.  PyTorch tensors are used as owners of device memory and for the
+current HIP stream, nothing else.  There is no CPU fallback: a missing library raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+from . import build as _build
+
+_lib = None
+
+OK = 0
+STATUS_NAMES = ["SQLLM_OK", "SQLLM_ERR_NULL", "SQLLM_ERR_BITS", "SQLLM_ERR_SHAPE", "SQLLM_ERR_ALIGN", "SQLLM_ERR_NNZ",
+                "SQLLM_ERR_BATCH", "SQLLM_ERR_HIP", "SQLLM_ERR_DEVICE"]
+
+EXPORTS = ["sqllm_lut_gemv", "sqllm_csr_spmv", "sqllm_dense_sparse_matvec", "sqllm_csr_spmv_rowwise",
+           "sqllm_unpack_indices", "sqllm_dequantize", "sqllm_fp16_gemv", "sqllm_algorithmic_bytes",
+           "sqllm_set_rows_per_workgroup", "sqllm_last_error_string", "sqllm_status_string", "sqllm_version"]
+
+
+class SqllmError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else status}: {message}")
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """Load libsqllm.so (built in-tree by build.py).  Builds it only if no library is there at all."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build()
+        L = ctypes.CDLL(_build.LIB)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong
+        L.sqllm_lut_gemv.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
+        L.sqllm_csr_spmv.argtypes = [i32, i32, i64, i32, vp, vp, vp, vp, vp, i32, vp]
+        L.sqllm_csr_spmv_rowwise.argtypes = [i32, i32, i64, i32, vp, vp, vp, vp, vp, i32, vp]
+        L.sqllm_dense_sparse_matvec.argtypes = [i32, i32, i32, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.sqllm_unpack_indices.argtypes = [i32, i32, i32, vp, vp, vp]
+        L.sqllm_dequantize.argtypes = [i32, i32, i32, vp, vp, vp, vp]
+        L.sqllm_fp16_gemv.argtypes = [i32, i32, i32, vp, vp, vp, vp]
+        L.sqllm_algorithmic_bytes.argtypes = [i32, i32, i32, i64, i32]
+        L.sqllm_algorithmic_bytes.restype = i64
+        L.sqllm_set_rows_per_workgroup.argtypes = [i32]
+        L.sqllm_last_error_string.restype = ctypes.c_char_p
+        L.sqllm_status_string.argtypes = [i32]
+        L.sqllm_status_string.restype = ctypes.c_char_p
+        for name in EXPORTS:
+            if getattr(L, name).restype is ctypes.c_int:
+                pass
+        _lib = L
+    return _lib
+
+
+def _check(status: int):
+    if status != OK:
+        raise SqllmError(status, lib().sqllm_last_error_string().decode())
+
+
+def _ptr(t):
+    """Device (or raw integer) pointer of a tensor; None -> NULL."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def sqllm_lut_gemv(M, N, bits, B, qidx, lut, x, y, accumulate=0, stream=None):
+    _check(lib().sqllm_lut_gemv(M, N, bits, B, _ptr(qidx), _ptr(lut), _ptr(x), _ptr(y), int(accumulate), _stream(stream)))
+
+
+def sqllm_csr_spmv(M, N, nnz, B, rowptr, cols, vals, x, y, accumulate=0, stream=None):
+    _check(lib().sqllm_csr_spmv(M, N, nnz, B, _ptr(rowptr), _ptr(cols), _ptr(vals), _ptr(x), _ptr(y), int(accumulate), _stream(stream)))
+
+
+def sqllm_csr_spmv_rowwise(M, N, nnz, B, rowptr, cols, vals, x, y, accumulate=0, stream=None):
+    _check(lib().sqllm_csr_spmv_rowwise(M, N, nnz, B, _ptr(rowptr), _ptr(cols), _ptr(vals), _ptr(x), _ptr(y), int(accumulate), _stream(stream)))
+
+
+def sqllm_dense_sparse_matvec(M, N, bits, nnz, B, qidx, lut, rowptr, cols, vals, x, y, stream=None):
+    _check(lib().sqllm_dense_sparse_matvec(M, N, bits, nnz, B, _ptr(qidx), _ptr(lut), _ptr(rowptr), _ptr(cols), _ptr(vals),
+                                           _ptr(x), _ptr(y), _stream(stream)))
+
+
+def sqllm_unpack_indices(M, N, bits, qidx, idx_out, stream=None):
+    _check(lib().sqllm_unpack_indices(M, N, bits, _ptr(qidx), _ptr(idx_out), _stream(stream)))
+
+
+def sqllm_dequantize(M, N, bits, qidx, lut, w_out, stream=None):
+    _check(lib().sqllm_dequantize(M, N, bits, _ptr(qidx), _ptr(lut), _ptr(w_out), _stream(stream)))
+
+
+def sqllm_fp16_gemv(M, N, B, w, x, y, stream=None):
+    _check(lib().sqllm_fp16_gemv(M, N, B, _ptr(w), _ptr(x), _ptr(y), _stream(stream)))
+
+
+def sqllm_algorithmic_bytes(M, N, bits, nnz, B) -> int:
+    return int(lib().sqllm_algorithmic_bytes(M, N, bits, nnz, B))
+
+
+def sqllm_set_rows_per_workgroup(rows: int) -> int:
+    return int(lib().sqllm_set_rows_per_workgroup(int(rows)))
+
+
+def sqllm_version() -> int:
+    return int(lib().sqllm_version())

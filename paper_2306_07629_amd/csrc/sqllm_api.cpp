@@ -1,0 +1,203 @@
+// Host side of the C ABI declared in sqllm.h: argument validation (everything that can be decided without
+// touching the device is decided here, before any HIP call), choice of launch shape, error reporting.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "sqllm.h"
+#include "sqllm_kernels.h"
+
+namespace {
+
+thread_local char g_err[256] = "no error";
+int g_rows_per_wg = 0;   // 0 = choose per shape
+
+int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+int fail(int status, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+int check_shape(int M, int N, int B) {
+    if (M < 0) return fail(SQLLM_ERR_SHAPE, "M = %d is negative", M);
+    if (N <= 0 || N % 128 != 0) return fail(SQLLM_ERR_SHAPE, "N = %d must be a positive multiple of 128", N);
+    if (N > SQLLM_MAX_N) return fail(SQLLM_ERR_SHAPE, "N = %d exceeds SQLLM_MAX_N = %d", N, SQLLM_MAX_N);
+    if (B < 1 || B > SQLLM_MAX_BATCH) return fail(SQLLM_ERR_BATCH, "B = %d outside 1..%d", B, SQLLM_MAX_BATCH);
+    return SQLLM_OK;
+}
+
+int check_bits(int bits) {
+    if (bits != 3 && bits != 4) return fail(SQLLM_ERR_BITS, "bits = %d, only 3 and 4 are supported", bits);
+    return SQLLM_OK;
+}
+
+int check_dense_ptrs(const void* qidx, const void* lut) {
+    if (!qidx || !lut) return fail(SQLLM_ERR_NULL, "qidx / lut must not be NULL");
+    if (misaligned(qidx, 16) || misaligned(lut, 16)) return fail(SQLLM_ERR_ALIGN, "qidx and lut must be 16-byte aligned");
+    return SQLLM_OK;
+}
+
+int check_xy(const void* x, const void* y) {
+    if (!x || !y) return fail(SQLLM_ERR_NULL, "x / y must not be NULL");
+    if (misaligned(x, 16)) return fail(SQLLM_ERR_ALIGN, "x must be 16-byte aligned");
+    if (misaligned(y, 2)) return fail(SQLLM_ERR_ALIGN, "y must be 2-byte aligned");
+    return SQLLM_OK;
+}
+
+int check_sparse(long long nnz, const int* rowptr, const int* cols, const void* vals) {
+    if (nnz < 0 || nnz > 0x7FFFFFFFll) return fail(SQLLM_ERR_NNZ, "nnz = %lld outside 0..2^31-1", nnz);
+    if (nnz == 0) return SQLLM_OK;
+    if (!rowptr || !cols || !vals) return fail(SQLLM_ERR_NULL, "rowptr / cols / vals must not be NULL when nnz > 0");
+    if (misaligned(rowptr, 4) || misaligned(cols, 4) || misaligned(vals, 2))
+        return fail(SQLLM_ERR_ALIGN, "rowptr and cols must be 4-byte aligned, vals 2-byte aligned");
+    return SQLLM_OK;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+    return fail(SQLLM_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// rows handled by one workgroup: aim at a few thousand waves in total so that every SIMD of the 256 compute
+// units holds several, while keeping enough rows per wave to amortise the activation load.
+int pick_rows(int M, int waves_per_wg) {
+    if (g_rows_per_wg > 0) return g_rows_per_wg;
+    const long long target_waves = 256ll * 4 * 6;
+    long long wgs = target_waves / waves_per_wg;
+    if (wgs < 1) wgs = 1;
+    long long rows = (M + wgs - 1) / wgs;
+    rows = (rows + 3) / 4 * 4;
+    if (rows < 4) rows = 4;
+    if (rows > 32) rows = 32;
+    return (int)rows;
+}
+
+int run_matvec(int M, int N, int bits, long long nnz, int B, const void* qidx, const void* lut, const int* rowptr,
+               const int* cols, const void* vals, const void* x, void* y, int accumulate, void* stream) {
+    if (M == 0) return SQLLM_OK;
+    sqllm::MatvecArgs g;
+    memset(&g, 0, sizeof g);
+    g.M = M; g.N = N; g.bits = bits; g.B = B; g.bt0 = 0; g.bn = B;
+    g.accumulate = accumulate; g.nnz = nnz;
+    g.qidx = qidx; g.lut = lut; g.rowptr = rowptr; g.cols = cols; g.vals = vals; g.x = x; g.y = y;
+    const int waves = qidx ? (N + 2047) / 2048 : 4;
+    g.rows_per_wg = qidx ? pick_rows(M, waves) : (g_rows_per_wg > 0 ? g_rows_per_wg : 32);
+    const hipError_t e = sqllm::launch_matvec(g, waves, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "matvec launch");
+    return SQLLM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sqllm_lut_gemv(int M, int N, int bits, int B, const void* qidx, const void* lut, const void* x, void* y,
+                   int accumulate, void* stream) {
+    int st;
+    if ((st = check_bits(bits)) || (st = check_shape(M, N, B)) || (st = check_dense_ptrs(qidx, lut)) || (st = check_xy(x, y))) return st;
+    return run_matvec(M, N, bits, 0, B, qidx, lut, nullptr, nullptr, nullptr, x, y, accumulate, stream);
+}
+
+int sqllm_csr_spmv(int M, int N, long long nnz, int B, const int* rowptr, const int* cols, const void* vals,
+                   const void* x, void* y, int accumulate, void* stream) {
+    int st;
+    if ((st = check_shape(M, N, B)) || (st = check_sparse(nnz, rowptr, cols, vals)) || (st = check_xy(x, y))) return st;
+    return run_matvec(M, N, 3, nnz, B, nullptr, nullptr, rowptr, cols, vals, x, y, accumulate, stream);
+}
+
+int sqllm_dense_sparse_matvec(int M, int N, int bits, long long nnz, int B, const void* qidx, const void* lut,
+                              const int* rowptr, const int* cols, const void* vals, const void* x, void* y, void* stream) {
+    int st;
+    if ((st = check_bits(bits)) || (st = check_shape(M, N, B)) || (st = check_dense_ptrs(qidx, lut)) ||
+        (st = check_sparse(nnz, rowptr, cols, vals)) || (st = check_xy(x, y))) return st;
+    return run_matvec(M, N, bits, nnz, B, qidx, lut, rowptr, cols, vals, x, y, 0, stream);
+}
+
+int sqllm_csr_spmv_rowwise(int M, int N, long long nnz, int B, const int* rowptr, const int* cols, const void* vals,
+                           const void* x, void* y, int accumulate, void* stream) {
+    int st;
+    if ((st = check_shape(M, N, B)) || (st = check_sparse(nnz, rowptr, cols, vals)) || (st = check_xy(x, y))) return st;
+    if (M == 0) return SQLLM_OK;
+    sqllm::MatvecArgs g;
+    memset(&g, 0, sizeof g);
+    g.M = M; g.N = N; g.bits = 3; g.B = B; g.bn = B; g.accumulate = accumulate; g.nnz = nnz;
+    g.rowptr = rowptr; g.cols = cols; g.vals = vals; g.x = x; g.y = y;
+    const hipError_t e = sqllm::launch_csr_rowwise(g, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "csr_rowwise launch");
+    return SQLLM_OK;
+}
+
+int sqllm_unpack_indices(int M, int N, int bits, const void* qidx, void* idx_out, void* stream) {
+    int st;
+    if ((st = check_bits(bits)) || (st = check_shape(M, N, 1))) return st;
+    if (!qidx || !idx_out) return fail(SQLLM_ERR_NULL, "qidx / idx_out must not be NULL");
+    if (misaligned(qidx, 16)) return fail(SQLLM_ERR_ALIGN, "qidx must be 16-byte aligned");
+    if (M == 0) return SQLLM_OK;
+    const hipError_t e = sqllm::launch_decode(M, N, bits, qidx, nullptr, idx_out, nullptr, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "unpack launch");
+    return SQLLM_OK;
+}
+
+int sqllm_dequantize(int M, int N, int bits, const void* qidx, const void* lut, void* w_out, void* stream) {
+    int st;
+    if ((st = check_bits(bits)) || (st = check_shape(M, N, 1)) || (st = check_dense_ptrs(qidx, lut))) return st;
+    if (!w_out) return fail(SQLLM_ERR_NULL, "w_out must not be NULL");
+    if (misaligned(w_out, 2)) return fail(SQLLM_ERR_ALIGN, "w_out must be 2-byte aligned");
+    if (M == 0) return SQLLM_OK;
+    const hipError_t e = sqllm::launch_decode(M, N, bits, qidx, lut, nullptr, w_out, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "dequantize launch");
+    return SQLLM_OK;
+}
+
+int sqllm_fp16_gemv(int M, int N, int B, const void* w, const void* x, void* y, void* stream) {
+    if (M < 0) return fail(SQLLM_ERR_SHAPE, "M = %d is negative", M);
+    if (N <= 0 || N % 8 != 0) return fail(SQLLM_ERR_SHAPE, "N = %d must be a positive multiple of 8", N);
+    if (B < 1 || B > SQLLM_MAX_BATCH) return fail(SQLLM_ERR_BATCH, "B = %d outside 1..%d", B, SQLLM_MAX_BATCH);
+    if (!w) return fail(SQLLM_ERR_NULL, "w must not be NULL");
+    if (misaligned(w, 16)) return fail(SQLLM_ERR_ALIGN, "w must be 16-byte aligned");
+    int st;
+    if ((st = check_xy(x, y))) return st;
+    if (M == 0) return SQLLM_OK;
+    const hipError_t e = sqllm::launch_fp16_gemv(M, N, B, w, x, y, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "fp16_gemv launch");
+    return SQLLM_OK;
+}
+
+long long sqllm_algorithmic_bytes(int M, int N, int bits, long long nnz, int B) {
+    long long b = (long long)M * N * bits / 8 + (long long)M * (1ll << bits) * 2 + (long long)B * ((long long)N + M) * 2;
+    if (nnz > 0) b += nnz * 6 + ((long long)M + 1) * 4;
+    return b;
+}
+
+int sqllm_set_rows_per_workgroup(int rows) {
+    const int old = g_rows_per_wg;
+    g_rows_per_wg = rows < 0 ? 0 : (rows > 64 ? 64 : rows);
+    return old;
+}
+
+const char* sqllm_last_error_string(void) { return g_err; }
+
+const char* sqllm_status_string(int status) {
+    switch (status) {
+        case SQLLM_OK: return "SQLLM_OK";
+        case SQLLM_ERR_NULL: return "SQLLM_ERR_NULL";
+        case SQLLM_ERR_BITS: return "SQLLM_ERR_BITS";
+        case SQLLM_ERR_SHAPE: return "SQLLM_ERR_SHAPE";
+        case SQLLM_ERR_ALIGN: return "SQLLM_ERR_ALIGN";
+        case SQLLM_ERR_NNZ: return "SQLLM_ERR_NNZ";
+        case SQLLM_ERR_BATCH: return "SQLLM_ERR_BATCH";
+        case SQLLM_ERR_HIP: return "SQLLM_ERR_HIP";
+        case SQLLM_ERR_DEVICE: return "SQLLM_ERR_DEVICE";
+        default: return "SQLLM_ERR_UNKNOWN";
+    }
+}
+
+int sqllm_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,108 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad arguments on the host
+(no kernel is launched by any test in this file)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2306_07629_amd as sq
+from paper_2306_07629_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+A = 1 << 20   # a fake, 16-byte aligned, never dereferenced device address
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "sqllm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sqllm_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = sq.lib()
+    names = header_symbols()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(binding.EXPORTS) == names
+    for n in names:                                   # the Python binding offers the same names
+        if n not in ("sqllm_last_error_string", "sqllm_status_string"):
+            assert hasattr(sq, n) or hasattr(binding, n), n
+    assert sq.sqllm_version() >= 100
+
+
+def expect(status_name, fn, *args):
+    with pytest.raises(sq.SqllmError) as e:
+        fn(*args, stream=0)
+    assert binding.STATUS_NAMES[e.value.status] == status_name, str(e.value)
+    assert len(str(e.value)) > len(status_name) + 2          # carries a message
+
+
+def test_lut_gemv_argument_errors():
+    f = sq.sqllm_lut_gemv
+    expect("SQLLM_ERR_BITS", f, 4, 128, 2, 1, A, A, A, A)
+    expect("SQLLM_ERR_BITS", f, 4, 128, 5, 1, A, A, A, A)
+    expect("SQLLM_ERR_SHAPE", f, -1, 128, 3, 1, A, A, A, A)
+    expect("SQLLM_ERR_SHAPE", f, 4, 0, 3, 1, A, A, A, A)
+    expect("SQLLM_ERR_SHAPE", f, 4, 100, 3, 1, A, A, A, A)
+    expect("SQLLM_ERR_SHAPE", f, 4, 64, 4, 1, A, A, A, A)
+    expect("SQLLM_ERR_SHAPE", f, 4, 32768 + 128, 3, 1, A, A, A, A)
+    expect("SQLLM_ERR_BATCH", f, 4, 128, 3, 0, A, A, A, A)
+    expect("SQLLM_ERR_BATCH", f, 4, 128, 3, 9, A, A, A, A)
+    expect("SQLLM_ERR_NULL", f, 4, 128, 3, 1, None, A, A, A)
+    expect("SQLLM_ERR_NULL", f, 4, 128, 3, 1, A, None, A, A)
+    expect("SQLLM_ERR_NULL", f, 4, 128, 3, 1, A, A, None, A)
+    expect("SQLLM_ERR_NULL", f, 4, 128, 3, 1, A, A, A, None)
+    expect("SQLLM_ERR_ALIGN", f, 4, 128, 3, 1, A + 4, A, A, A)
+    expect("SQLLM_ERR_ALIGN", f, 4, 128, 3, 1, A, A + 8, A, A)
+    expect("SQLLM_ERR_ALIGN", f, 4, 128, 3, 1, A, A, A + 2, A)
+    expect("SQLLM_ERR_ALIGN", f, 4, 128, 3, 1, A, A, A, A + 1)
+
+
+def test_sparse_argument_errors():
+    f = sq.sqllm_csr_spmv
+    expect("SQLLM_ERR_NNZ", f, 4, 128, -1, 1, A, A, A, A, A)
+    expect("SQLLM_ERR_NNZ", f, 4, 128, 1 << 31, 1, A, A, A, A, A)
+    expect("SQLLM_ERR_NULL", f, 4, 128, 5, 1, None, A, A, A, A)
+    expect("SQLLM_ERR_NULL", f, 4, 128, 5, 1, A, None, A, A, A)
+    expect("SQLLM_ERR_NULL", f, 4, 128, 5, 1, A, A, None, A, A)
+    expect("SQLLM_ERR_ALIGN", f, 4, 128, 5, 1, A + 2, A, A, A, A)
+    expect("SQLLM_ERR_ALIGN", f, 4, 128, 5, 1, A, A, A + 1, A, A)
+    expect("SQLLM_ERR_SHAPE", f, 4, 130, 5, 1, A, A, A, A, A)
+    g = sq.sqllm_dense_sparse_matvec
+    expect("SQLLM_ERR_NULL", g, 4, 128, 3, 5, 1, A, A, None, A, A, A, A)
+    expect("SQLLM_ERR_BITS", g, 4, 128, 8, 5, 1, A, A, A, A, A, A, A)
+    expect("SQLLM_ERR_NNZ", g, 4, 128, 3, -2, 1, A, A, A, A, A, A, A)
+    expect("SQLLM_ERR_BATCH", g, 4, 128, 3, 0, 100, A, A, None, None, None, A, A)
+    h = sq.sqllm_csr_spmv_rowwise
+    expect("SQLLM_ERR_NNZ", h, 4, 128, -1, 1, A, A, A, A, A)
+
+
+def test_debug_and_baseline_argument_errors():
+    expect("SQLLM_ERR_NULL", sq.sqllm_unpack_indices, 4, 128, 3, A, None)
+    expect("SQLLM_ERR_BITS", sq.sqllm_unpack_indices, 4, 128, 1, A, A)
+    expect("SQLLM_ERR_NULL", sq.sqllm_dequantize, 4, 128, 4, A, A, None)
+    expect("SQLLM_ERR_ALIGN", sq.sqllm_dequantize, 4, 128, 4, A, A, A + 1)
+    expect("SQLLM_ERR_SHAPE", sq.sqllm_fp16_gemv, 4, 12, 1, A, A, A)
+    expect("SQLLM_ERR_NULL", sq.sqllm_fp16_gemv, 4, 16, 1, None, A, A)
+    expect("SQLLM_ERR_ALIGN", sq.sqllm_fp16_gemv, 4, 16, 1, A + 2, A, A)
+    expect("SQLLM_ERR_BATCH", sq.sqllm_fp16_gemv, 4, 16, 0, A, A, A)
+
+
+def test_empty_problem_is_ok_without_a_device():
+    # M == 0: nothing to do, nothing is enqueued, no HIP call is made
+    sq.sqllm_lut_gemv(0, 128, 3, 1, A, A, A, A, stream=0)
+    sq.sqllm_dense_sparse_matvec(0, 128, 4, 0, 1, A, A, None, None, None, A, A, stream=0)
+    sq.sqllm_csr_spmv(0, 128, 0, 1, None, None, None, A, A, stream=0)
+    sq.sqllm_unpack_indices(0, 128, 3, A, A, stream=0)
+
+
+def test_algorithmic_bytes_and_status_strings():
+    assert sq.sqllm_algorithmic_bytes(11008, 4096, 3, 202899, 1) == 18376054
+    assert sq.sqllm_algorithmic_bytes(4096, 4096, 4, 75497, 1) == 9005434
+    assert sq.sqllm_algorithmic_bytes(4096, 4096, 4, 0, 1) == 4096 * 4096 // 2 + 4096 * 32 + 2 * 8192
+    L = sq.lib()
+    assert L.sqllm_status_string(0) == b"SQLLM_OK" and L.sqllm_status_string(3) == b"SQLLM_ERR_SHAPE"
+    old = sq.sqllm_set_rows_per_workgroup(8)
+    assert sq.sqllm_set_rows_per_workgroup(old) == 8
