@@ -42,15 +42,37 @@ def parse():
     ap.add_argument("--footprint-gb", type=float, default=1.1, help="bytes of distinct weight copies to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rows-per-wg", type=int, default=0)
+    ap.add_argument("--no-graph", action="store_true", help="issue every launch from Python instead of replaying a HIP graph")
     return ap.parse_args()
 
 
-def time_steps(torch, fn, steps, warmup):
-    """K calls of fn(step) bracketed by device synchronisation; HIP events on the launch stream."""
+def time_steps(torch, fn, steps, warmup, use_graph=True):
+    """W untimed + exactly K timed calls of fn(step), bracketed by device synchronisation, timed with HIP
+    events on the launch stream.  With use_graph the K launches are first captured into one HIP graph
+    (still K separate kernel launches, executed in order on one stream) so that the Python/ctypes cost of
+    issuing a launch (about 10 us, more than the kernel itself) is not what is measured."""
     for s in range(warmup):
         fn(s)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if use_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for s in range(steps):
+                    fn(warmup + s)
+            torch.cuda.synchronize()
+            graph.replay()                       # untimed first replay (uploads the graph)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e0.record()
+            graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+        return e0.elapsed_time(e1) * 1e-3, wall
     t0 = time.perf_counter()
     e0.record()
     for s in range(steps):
@@ -109,8 +131,9 @@ def main():
         for D in dev:
             D.matvec()
 
-    sec_cold, wall_cold = time_steps(torch, step_cold, args.steps, args.warmup)
-    sec_warm, _ = time_steps(torch, step_warm, args.steps, args.warmup)
+    G = not args.no_graph
+    sec_cold, wall_cold = time_steps(torch, step_cold, args.steps, args.warmup, G)
+    sec_warm, _ = time_steps(torch, step_warm, args.steps, args.warmup, G)
     launches = args.steps * len(shapes)
     us_per_matvec = sec_cold / launches * 1e6
     gbs = step_bytes * args.steps / sec_cold / 1e9
@@ -133,8 +156,8 @@ def main():
             torch.mv(wring[k][c], xs[k], out=ys[k])
 
     fsteps = max(20, args.steps // 4)
-    sec_f_own, _ = time_steps(torch, step_fp16_own, fsteps, 10)
-    sec_f_torch, _ = time_steps(torch, step_fp16_torch, fsteps, 10)
+    sec_f_own, _ = time_steps(torch, step_fp16_own, fsteps, 10, G)
+    sec_f_torch, _ = time_steps(torch, step_fp16_torch, fsteps, 10, G)
     us_f_own = sec_f_own / (fsteps * len(shapes)) * 1e6
     us_f_torch = sec_f_torch / (fsteps * len(shapes)) * 1e6
     us_f = min(us_f_own, us_f_torch)
@@ -178,7 +201,7 @@ def main():
         "effective_gbs": gbs, "pct_of_hbm_roofline": 100.0 * gbs / HBM_PEAK_GBS,
         "warm_us_per_matvec": sec_warm / launches * 1e6, "warm_effective_gbs": step_bytes * args.steps / sec_warm / 1e9,
         "fp16_gemv_us": {"own_kernel": us_f_own, "torch_mv": us_f_torch}, "speedup_vs_fp16": us_f / us_per_matvec,
-        "parity_worst_err_over_bound": worst, "host_wall_s_timed_region": wall_cold,
+        "parity_worst_err_over_bound": worst, "launch_mode": "hip_graph_replay" if G else "python_ctypes", "host_wall_s_timed_region": wall_cold,
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                      "traffic": traffic, "kernel": f"sqllm::matvec_kernel<{bits},1,*>",
                      "algorithmic_bytes_per_launch": step_bytes / len(shapes)},

@@ -13,6 +13,7 @@ namespace {
 
 thread_local char g_err[256] = "no error";
 int g_rows_per_wg = 0;   // 0 = choose per shape
+int g_prefetch_rows = 0;  // 0 = library default
 
 int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 int fail(int status, const char* fmt, ...) {
@@ -64,18 +65,13 @@ int hip_fail(hipError_t e, const char* what) {
     return fail(SQLLM_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-// rows handled by one workgroup: aim at a few thousand waves in total so that every SIMD of the 256 compute
-// units holds several, while keeping enough rows per wave to amortise the activation load.
+// Rows handled by one workgroup (the kernels are built for 2, 4, 8 and 16).  Measured on MI355X at the
+// LLaMA-7B shapes: 4 rows is the fastest -- the whole matrix is requested within the first microsecond and
+// the time after the last byte arrives is the decode time of one workgroup, which grows with its row count.
 int pick_rows(int M, int waves_per_wg) {
     if (g_rows_per_wg > 0) return g_rows_per_wg;
-    const long long target_waves = 256ll * 4 * 6;
-    long long wgs = target_waves / waves_per_wg;
-    if (wgs < 1) wgs = 1;
-    long long rows = (M + wgs - 1) / wgs;
-    rows = (rows + 3) / 4 * 4;
-    if (rows < 4) rows = 4;
-    if (rows > 32) rows = 32;
-    return (int)rows;
+    (void)M; (void)waves_per_wg;
+    return 4;
 }
 
 int run_matvec(int M, int N, int bits, long long nnz, int B, const void* qidx, const void* lut, const int* rowptr,
@@ -86,9 +82,10 @@ int run_matvec(int M, int N, int bits, long long nnz, int B, const void* qidx, c
     g.M = M; g.N = N; g.bits = bits; g.B = B; g.bt0 = 0; g.bn = B;
     g.accumulate = accumulate; g.nnz = nnz;
     g.qidx = qidx; g.lut = lut; g.rowptr = rowptr; g.cols = cols; g.vals = vals; g.x = x; g.y = y;
-    const int waves = qidx ? (N + 2047) / 2048 : 4;
-    g.rows_per_wg = qidx ? pick_rows(M, waves) : (g_rows_per_wg > 0 ? g_rows_per_wg : 32);
-    const hipError_t e = sqllm::launch_matvec(g, waves, static_cast<hipStream_t>(stream));
+    const int waves = qidx ? (N + 2047) / 2048 : 0;
+    g.rows_per_wg = pick_rows(M, waves);
+    g.prefetch_rows = g_prefetch_rows > 0 ? g_prefetch_rows : 4;
+    const hipError_t e = sqllm::launch_matvec(g, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "matvec launch");
     return SQLLM_OK;
 }
@@ -178,6 +175,12 @@ long long sqllm_algorithmic_bytes(int M, int N, int bits, long long nnz, int B) 
 int sqllm_set_rows_per_workgroup(int rows) {
     const int old = g_rows_per_wg;
     g_rows_per_wg = rows < 0 ? 0 : (rows > 64 ? 64 : rows);
+    return old;
+}
+
+int sqllm_set_prefetch_rows(int rows) {
+    const int old = g_prefetch_rows;
+    g_prefetch_rows = rows < 0 ? 0 : (rows > 16 ? 16 : rows);
     return old;
 }
 

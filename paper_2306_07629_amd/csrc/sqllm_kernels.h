@@ -7,7 +7,8 @@ namespace sqllm {
 struct MatvecArgs {
     int M, N, bits, B;
     int bt0, bn;            // batch columns [bt0, bt0 + bn) are computed by this launch (bn <= 4)
-    int rows_per_wg;
+    int rows_per_wg;        // requested rows per workgroup; the launcher rounds it to 4, 8 or 16
+    int prefetch_rows;      // index-stream rows in flight per wave (rounded to 2, 4 or 8)
     int accumulate;
     long long nnz;
     const void* qidx;       // nullptr -> no dense term
@@ -19,7 +20,7 @@ struct MatvecArgs {
     void* y;
 };
 
-hipError_t launch_matvec(const MatvecArgs& g, int waves, hipStream_t s);
+hipError_t launch_matvec(const MatvecArgs& g, hipStream_t s);
 hipError_t launch_csr_rowwise(const MatvecArgs& g, hipStream_t s);
 hipError_t launch_decode(int M, int N, int bits, const void* qidx, const void* lut, void* idx_out, void* w_out, hipStream_t s);
 hipError_t launch_fp16_gemv(int M, int N, int B, const void* w, const void* x, void* y, hipStream_t s);

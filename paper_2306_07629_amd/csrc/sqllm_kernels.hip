@@ -3,26 +3,29 @@
 // What is computed (paper Sec. 4.2-4.3):  y = D x + S x,  D[i][j] = lut[i][idx(i,j)] with b-bit indices and
 // one fp16 table per output row, S in CSR with fp16 values.  The storage format is described in sqllm.h.
 //
-// Work decomposition
-//   * A wave owns a slice of 2048 consecutive columns: lane l holds the 32 activations
-//     x[2048 w + 32 l .. +32) in registers for the whole kernel, so x is read once per workgroup.
-//   * A workgroup has W = ceil(N / 2048) waves (one per slice) and walks over `rows_per_wg` consecutive
-//     rows.  For every row each lane loads its 32 indices (12 bytes for b = 3, 16 bytes for b = 4: the
-//     wave reads 768 / 1024 contiguous bytes per row), decodes them in registers and accumulates in fp32.
-//   * Table look-ups never touch LDS memory: the row's table lives in ONE register spread over the 64
-//     lanes and is read with ds_bpermute_b32 (a cross-lane gather that has no bank conflicts).
-//       b = 3: lane e holds the pair (lut[e & 7], lut[e >> 3]); a 6-bit field of the stream (two
-//              neighbouring indices) selects a ready-made fp16 pair that feeds v_dot2_f32_f16.
-//       b = 4: lane e holds lut[e & 15]; one look-up per index, fp16 x fp16 -> fp32 fused multiply-add.
-//     The gather address is (field << 2); the hardware uses address bits [7:2] only, so a single shift (or a
-//     funnel shift where a field straddles two dwords) per look-up is all the integer work there is.
-//   * Per row the 64 lane sums are reduced with DPP adds, the W slice sums are combined through LDS in a
-//     fixed order, the CSR term is added, and y is rounded to fp16 once.
-//   * CSR term (balanced): the nonzeros of the workgroup's rows form one contiguous range of the CSR
-//     arrays; thread t takes nonzeros t, t + T, t + 2T, ... of that range whatever rows they fall in
-//     (equal work per thread), products are combined per row with a segmented scan inside the wave and
-//     accumulated into wave-private LDS slots, so no floating-point atomics are needed and the result does
-//     not depend on timing.
+// Work decomposition of the matvec kernel
+//   * A workgroup owns R consecutive rows (R = 4, 8 or 16, compile time) and all N columns.
+//   * Dense waves: wave w owns the 2048-column slice [2048 w, 2048 w + 2048): lane l keeps the 32 activations
+//     x[2048 w + 32 l .. +32) in registers for the whole kernel (x is read once per workgroup) and, per row,
+//     loads its 32 indices (12 bytes for b = 3, 16 bytes for b = 4; the wave reads 768 / 1024 contiguous
+//     bytes of the row).  All R row loads are issued before the first is consumed.
+//   * Dequantisation goes through PAIR TABLES in LDS: for every row of the block the workgroup first builds
+//       b = 3:  64 entries,  entry (a | c << 3) = (lut[a], lut[c]) as two fp16 in one dword   (256 B / row)
+//       b = 4: 256 entries,  entry (a | c << 4) = (lut[a], lut[c])                            (1 KB / row)
+//     so ONE ds_read_b32, addressed by a 6- or 8-bit field of the index stream (two neighbouring indices),
+//     returns a ready-made fp16 pair for v_dot2_f32_f16 (two products, fp32 accumulate).  Measured on MI355X
+//     this costs ~2.1 (64 entries) / ~5.5 (256 entries) LDS cycles per wave-wide look-up of 128 weights,
+//     against ~7.3 for a ds_bpermute-based register table.  The field extraction is a shift + mask
+//     (a funnel shift where a 3-bit pair straddles two dwords; a byte select for b = 4).
+//   * Per row the 64 lane sums are reduced with DPP adds (no LDS traffic), the slice sums of the W waves
+//     are combined through LDS in a fixed order, the CSR term is added, and y is rounded to fp16 once.
+//   * Sparse wave (balanced CSR, cf. Sec. 4.3): one extra wave per workgroup handles the nonzeros of the
+//     block's rows while the dense waves stream.  The nonzeros of R consecutive rows are one contiguous
+//     range of the CSR arrays; lane l takes nonzeros l, l + 64, ... of that range whatever rows they fall in
+//     (equal work per lane), finds each one's row by comparing against the R + 1 row pointers held in
+//     scalar registers, and the products are combined per row with a segmented scan built from DPP moves.
+//     Only the last lane of each row segment touches the row's LDS accumulator, so no floating-point
+//     atomics are needed and the result does not depend on timing.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -38,25 +41,44 @@ typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kWave = 64;
 constexpr int kLaneElems = 32;                      // indices per lane per row
 constexpr int kSliceCols = kWave * kLaneElems;      // 2048 columns per wave
+constexpr int kMaxDenseWaves = 15;                  // N <= 30720
 
 // ---------------------------------------------------------------------------------------------- helpers
 __device__ __forceinline__ u32 funnel_shr(u32 hi, u32 lo, u32 sh) { return __builtin_amdgcn_alignbit(hi, lo, sh); }
+__device__ __forceinline__ half2_t as_half2(u32 v) { return __builtin_bit_cast(half2_t, v); }
+__device__ __forceinline__ float half_bits_to_float(uint16_t h) { return (float)__builtin_bit_cast(half_t, h); }
+__device__ __forceinline__ uint16_t float_to_half_bits(float f) { return __builtin_bit_cast(uint16_t, (half_t)f); }
 
-__device__ __forceinline__ u32 lane_gather(u32 byte_addr, u32 table) {
-    return (u32)__builtin_amdgcn_ds_bpermute((int)byte_addr, (int)table);
+// DPP controls (gfx9 encoding)
+constexpr int kQuadXor1 = 0xB1;        // quad_perm:[1,0,3,2]
+constexpr int kQuadXor2 = 0x4E;        // quad_perm:[2,3,0,1]
+constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr4 = 0x114, kRowShr8 = 0x118;
+constexpr int kWaveShl1 = 0x130;       // lane i reads lane i + 1
+constexpr int kRowRor4 = 0x124, kRowRor8 = 0x128;
+constexpr int kRowMirror = 0x140, kRowHalfMirror = 0x141;
+constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_f(float old, float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old), __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false));
+}
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ int dpp_i(int old, int v) {
+    return __builtin_amdgcn_update_dpp(old, v, CTRL, ROW_MASK, 0xF, false);
 }
 
-__device__ __forceinline__ half2_t as_half2(u32 v) { return __builtin_bit_cast(half2_t, v); }
-__device__ __forceinline__ u32 as_u32(half2_t v) { return __builtin_bit_cast(u32, v); }
-
-// sum over the 64 lanes; the total ends up in every lane
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
+// Sum over the 64 lanes without LDS traffic; the total is valid in lane 63.
+__device__ __forceinline__ float wave_sum_to_lane63(float v) {
+    v += dpp_f<kQuadXor1>(0.f, v);
+    v += dpp_f<kQuadXor2>(0.f, v);
+    v += dpp_f<kRowHalfMirror>(0.f, v);
+    v += dpp_f<kRowMirror>(0.f, v);                 // every lane: sum of its row of 16
+    v += dpp_f<kRowBcast15, 0xA>(0.f, v);           // rows 1 and 3 add the row before them
+    v += dpp_f<kRowBcast31, 0xC>(0.f, v);           // rows 2 and 3 add lane 31 (= rows 0 + 1)
     return v;
 }
 
-// ---------------------------------------------------------------------------------------------- decode
+// ---------------------------------------------------------------------------------------------- index stream
 // A lane's share of one row: BITS dwords = 32 indices.
 template <int BITS>
 struct LaneChunk {
@@ -64,229 +86,312 @@ struct LaneChunk {
 };
 
 template <int BITS>
-__device__ __forceinline__ LaneChunk<BITS> load_chunk(const u32* __restrict__ p, bool live) {
+__device__ __forceinline__ LaneChunk<BITS> load_chunk(const u32* __restrict__ p) {
     LaneChunk<BITS> c;
 #pragma unroll
-    for (int k = 0; k < BITS; ++k) c.q[k] = 0;
-    if (live) {
-#pragma unroll
-        for (int k = 0; k < BITS; ++k) c.q[k] = __builtin_nontemporal_load(p + k);
-    }
+    for (int k = 0; k < BITS; ++k) c.q[k] = __builtin_nontemporal_load(p + k);
     return c;
 }
 
-// b = 3.  Gather addresses of the 16 index PAIRS of a lane: pair p owns bits [6p, 6p+6) of the 96-bit
-// chunk; the address must carry that field in bits [7:2].
-__device__ __forceinline__ void pair_addresses(const LaneChunk<3>& c, u32 (&a)[16]) {
+// Byte offsets (entry * 4) into the row's pair table of the 16 index pairs of a lane.
+//   b = 3: pair p owns bits [6p, 6p + 6) of the 96-bit chunk; two of them straddle a dword boundary.
+//   b = 4: pair p is byte p of the 128-bit chunk.
+__device__ __forceinline__ void pair_offsets(const LaneChunk<3>& c, u32 (&a)[16]) {
     const u32 q0 = c.q[0], q1 = c.q[1], q2 = c.q[2];
-    a[0] = q0 << 2;   a[1] = q0 >> 4;   a[2] = q0 >> 10;  a[3] = q0 >> 16;  a[4] = q0 >> 22;
-    a[5] = funnel_shr(q1, q0, 28);                      // bits 30..35 straddle dwords 0 and 1
-    a[6] = q1 >> 2;   a[7] = q1 >> 8;   a[8] = q1 >> 14;  a[9] = q1 >> 20;
-    a[10] = funnel_shr(q2, q1, 26);                     // bits 60..65 straddle dwords 1 and 2
-    a[11] = q2;       a[12] = q2 >> 6;  a[13] = q2 >> 12; a[14] = q2 >> 18; a[15] = q2 >> 24;
+    a[0] = (q0 << 2) & 0xFC;   a[1] = (q0 >> 4) & 0xFC;   a[2] = (q0 >> 10) & 0xFC;  a[3] = (q0 >> 16) & 0xFC;
+    a[4] = (q0 >> 22) & 0xFC;
+    a[5] = funnel_shr(q1, q0, 28) & 0xFC;               // bits 30..35 straddle dwords 0 and 1
+    a[6] = (q1 >> 2) & 0xFC;   a[7] = (q1 >> 8) & 0xFC;   a[8] = (q1 >> 14) & 0xFC;  a[9] = (q1 >> 20) & 0xFC;
+    a[10] = funnel_shr(q2, q1, 26) & 0xFC;              // bits 60..65 straddle dwords 1 and 2
+    a[11] = q2 & 0xFC;         a[12] = (q2 >> 6) & 0xFC;  a[13] = (q2 >> 12) & 0xFC; a[14] = (q2 >> 18) & 0xFC;
+    a[15] = (q2 >> 24) & 0xFC;
+}
+__device__ __forceinline__ void pair_offsets(const LaneChunk<4>& c, u32 (&a)[16]) {
+#pragma unroll
+    for (int p = 0; p < 16; ++p) a[p] = ((c.q[p >> 2] >> (8 * (p & 3))) & 0xFF) << 2;
 }
 
-// b = 4.  Gather address of index k (0..31) of a lane: field bits [4k, 4k+4) -> address bits [5:2]
-// (bits [7:6] then carry part of the next index; the table is replicated four times so they do not matter).
-__device__ __forceinline__ u32 elem_address(const LaneChunk<4>& c, int k) {
-    const u32 q = c.q[k >> 3];
-    const int pos = k & 7;
-    return pos == 0 ? (q << 2) : (q >> (4 * pos - 2));
-}
-
-// The row's table, one register across the wave.
 template <int BITS>
-__device__ __forceinline__ u32 load_table(const uint16_t* __restrict__ lut_row, int lane);
+struct TableShape {
+    static constexpr int kEntryBits = 2 * BITS;               // 6 or 8
+    static constexpr int kEntries = 1 << kEntryBits;          // 64 or 256
+    static constexpr int kRowBytes = 2 << BITS;               // bytes of one row's fp16 table: 16 or 32
+};
 
-template <>
-__device__ __forceinline__ u32 load_table<3>(const uint16_t* __restrict__ lut_row, int lane) {
-    const u32 lo = lut_row[lane & 7], hi = lut_row[lane >> 3];
-    return lo | (hi << 16);
-}
-template <>
-__device__ __forceinline__ u32 load_table<4>(const uint16_t* __restrict__ lut_row, int lane) {
-    const u32 v = lut_row[lane & 15];
-    return v | (v << 16);
+// Pair tables of R rows from their fp16 tables staged in LDS (raw[u << BITS | k]); executed by ONE wave.
+template <int BITS, int R>
+__device__ __forceinline__ void build_tables(u32* __restrict__ tables, const uint16_t* __restrict__ raw, int lane) {
+    constexpr int E = TableShape<BITS>::kEntries, K = 1 << BITS;
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+        const u32 lo = raw[u * K + (lane & (K - 1))];           // the same for all entries of this lane
+#pragma unroll
+        for (int e0 = 0; e0 < E; e0 += kWave) {
+            const int e = e0 + lane;
+            const u32 hi = raw[u * K + (e >> BITS)];
+            tables[u * E + e] = lo | (hi << 16);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------- x in registers
-// xr[t][p] = (x[j0 + 2p][t], x[j0 + 2p + 1][t]) for the lane's 32 columns j0 .. j0 + 31.
+// xr[t][p] = (x[j0 + 2p][t], x[j0 + 2p + 1][t]) for the lane's 32 columns j0 .. j0 + 31 (j0 is in range).
 template <int NB>
-__device__ __forceinline__ void load_x(const uint16_t* __restrict__ x, int B, int bn, int j0, bool live, u32 (&xr)[NB][16]) {
-#pragma unroll
-    for (int t = 0; t < NB; ++t)
-#pragma unroll
-        for (int p = 0; p < 16; ++p) xr[t][p] = 0;
-    if (!live) return;
+__device__ __forceinline__ void load_x(const uint16_t* __restrict__ x, int B, int bn, int j0, u32 (&xr)[NB][16]) {
     if (NB == 1 && B == 1) {
-        const uint4* src = reinterpret_cast<const uint4*>(x + j0);
+        const u32x4* src = reinterpret_cast<const u32x4*>(x + j0);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const uint4 v = src[k];
+            const u32x4 v = src[k];
             xr[0][4 * k + 0] = v.x; xr[0][4 * k + 1] = v.y; xr[0][4 * k + 2] = v.z; xr[0][4 * k + 3] = v.w;
         }
     } else {
 #pragma unroll
         for (int t = 0; t < NB; ++t) {
-            if (t < bn) {
+            const int tc = t < bn ? t : 0;                          // clamp, zeroed below
 #pragma unroll
-                for (int p = 0; p < 16; ++p) {
-                    const u32 lo = x[(size_t)(j0 + 2 * p) * B + t], hi = x[(size_t)(j0 + 2 * p + 1) * B + t];
-                    xr[t][p] = lo | (hi << 16);
-                }
+            for (int p = 0; p < 16; ++p) {
+                const u32 lo = x[(size_t)(j0 + 2 * p) * B + tc], hi = x[(size_t)(j0 + 2 * p + 1) * B + tc];
+                xr[t][p] = t < bn ? (lo | (hi << 16)) : 0u;
             }
         }
     }
 }
 
-// ---------------------------------------------------------------------------------------------- dense row slice
-template <int BITS, int NB>
-__device__ __forceinline__ void accumulate_chunk(const LaneChunk<BITS>& c, u32 table, const u32 (&xr)[NB][16], float (&acc)[NB]);
-
-template <int NB>
-__device__ __forceinline__ void accumulate_chunk3(const LaneChunk<3>& c, u32 table, const u32 (&xr)[NB][16], float (&acc)[NB]) {
+// table look-ups of one row slice: 16 dwords, each an fp16 pair
+template <int BITS>
+__device__ __forceinline__ void lookup_chunk(const LaneChunk<BITS>& c, const u32* __restrict__ table, u32 (&w)[16]) {
     u32 a[16];
-    pair_addresses(c, a);
-    u32 w[16];
+    pair_offsets(c, a);
+    const char* tb = reinterpret_cast<const char*>(table);
 #pragma unroll
-    for (int p = 0; p < 16; ++p) w[p] = lane_gather(a[p], table);
-#pragma unroll
-    for (int p = 0; p < 16; ++p)
-#pragma unroll
-        for (int t = 0; t < NB; ++t) acc[t] = __builtin_amdgcn_fdot2(as_half2(w[p]), as_half2(xr[t][p]), acc[t], false);
+    for (int p = 0; p < 16; ++p) w[p] = *reinterpret_cast<const u32*>(tb + a[p]);
 }
 
+// 16 * NB packed dot products (two fp16 products each, fp32 accumulate); two accumulator chains per column
 template <int NB>
-__device__ __forceinline__ void accumulate_chunk4(const LaneChunk<4>& c, u32 table, const u32 (&xr)[NB][16], float (&acc)[NB]) {
+__device__ __forceinline__ void dot_chunk(const u32 (&w)[16], const u32 (&xr)[NB][16], float (&acc)[NB]) {
 #pragma unroll
-    for (int k = 0; k < 32; k += 2) {
-        const u32 w0 = lane_gather(elem_address(c, k), table);
-        const u32 w1 = lane_gather(elem_address(c, k + 1), table);
-        const float f0 = (float)as_half2(w0).x, f1 = (float)as_half2(w1).x;
+    for (int t = 0; t < NB; ++t) {
+        float a0 = 0.f, a1 = 0.f;
 #pragma unroll
-        for (int t = 0; t < NB; ++t) {
-            const half2_t xv = as_half2(xr[t][k >> 1]);
-            acc[t] = __builtin_fmaf(f0, (float)xv.x, acc[t]);
-            acc[t] = __builtin_fmaf(f1, (float)xv.y, acc[t]);
+        for (int p = 0; p < 16; p += 2) {
+            a0 = __builtin_amdgcn_fdot2(as_half2(w[p]), as_half2(xr[t][p]), a0, false);
+            a1 = __builtin_amdgcn_fdot2(as_half2(w[p + 1]), as_half2(xr[t][p + 1]), a1, false);
         }
+        acc[t] = a0 + a1;
     }
 }
 
-template <int BITS, int NB>
-__device__ __forceinline__ void accumulate_any(const LaneChunk<BITS>& c, u32 table, const u32 (&xr)[NB][16], float (&acc)[NB]) {
-    if constexpr (BITS == 3) accumulate_chunk3<NB>(c, table, xr, acc);
-    else accumulate_chunk4<NB>(c, table, xr, acc);
+// Joint reduction of C per-lane values over the lanes of each 16-lane row (C = 4, 8 or 16).  On return v[0]
+// of lane l holds, for class (l mod C), the sum of the input v[l mod C] over the 16 lanes of l's row.
+// log2(C) butterfly steps halve the number of live values; 3 VALU per produced value instead of a full
+// 6-step reduction per input.
+template <int C>
+__device__ __forceinline__ void row_block_reduce(float (&v)[C], int lane) {
+    static_assert(C == 2 || C == 4 || C == 8 || C == 16, "block size");
+    {   // lane bit 0, partner lane ^ 1
+        const bool hi = lane & 1;
+#pragma unroll
+        for (int k = 0; k < C / 2; ++k) {
+            const float keep = hi ? v[2 * k + 1] : v[2 * k], send = hi ? v[2 * k] : v[2 * k + 1];
+            v[k] = keep + dpp_f<kQuadXor1>(0.f, send);
+        }
+    }
+    if constexpr (C >= 4) {   // lane bit 1, partner lane ^ 2
+        const bool hi = lane & 2;
+#pragma unroll
+        for (int k = 0; k < C / 4; ++k) {
+            const float keep = hi ? v[2 * k + 1] : v[2 * k], send = hi ? v[2 * k] : v[2 * k + 1];
+            v[k] = keep + dpp_f<kQuadXor2>(0.f, send);
+        }
+    } else {
+        v[0] += dpp_f<kQuadXor2>(0.f, v[0]);
+    }
+    if constexpr (C >= 8) {   // lane bit 2: values travel by a rotation of 4 lanes within the row
+        const bool hi = lane & 4;
+#pragma unroll
+        for (int k = 0; k < C / 8; ++k) {
+            const float keep = hi ? v[2 * k + 1] : v[2 * k], send = hi ? v[2 * k] : v[2 * k + 1];
+            v[k] = keep + dpp_f<kRowRor4>(0.f, send);
+        }
+    } else {
+        v[0] += dpp_f<kRowRor4>(0.f, v[0]);
+    }
+    if constexpr (C == 16) {  // lane bit 3: rotation of 8 lanes
+        const bool hi = lane & 8;
+        const float keep = hi ? v[1] : v[0], send = hi ? v[0] : v[1];
+        v[0] = keep + dpp_f<kRowRor8>(0.f, send);
+    } else {
+        v[0] += dpp_f<kRowRor8>(0.f, v[0]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------- sparse wave
+// Nonzeros [P0, P1) of rows r0 .. r0 + R - 1; rp[k] = rowptr[r0 + k] (uniform, rp[k] = P1 beyond the last row).
+// Lane l takes nonzeros P0 + l, P0 + l + 64, ...; UNR batches of 64 are loaded before the first is reduced.
+// Row sums are added into sacc[row * NB + t] by the last lane of each row segment.
+template <int NB, int R>
+__device__ __forceinline__ void sparse_rows(const MatvecArgs& g, const uint16_t* __restrict__ x, int lane, const int (&rp)[R + 1], float* __restrict__ sacc) {
+    const int P0 = rp[0], P1 = rp[R];
+    const int* __restrict__ cols = g.cols;
+    const uint16_t* __restrict__ vals = static_cast<const uint16_t*>(g.vals);
+    const int B = g.B, bn = g.bn;
+    constexpr int UNR = NB == 1 ? 8 : (NB == 2 ? 4 : 2);
+    for (int pb = P0; pb < P1; pb += UNR * kWave) {                // uniform
+        int c[UNR]; uint16_t vb[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int p = min(pb + u * kWave + lane, P1 - 1);       // clamped, masked below
+            c[u] = cols[p];
+            vb[u] = vals[p];
+        }
+        uint16_t xb[UNR][NB];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u)
+#pragma unroll
+            for (int t = 0; t < NB; ++t) xb[u][t] = x[(size_t)c[u] * B + (t < bn ? t : 0)];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            if (pb + u * kWave >= P1) break;                       // uniform
+            const int p = pb + u * kWave + lane;
+            const bool ok = p < P1;
+            int row = 0;                                           // number of k in 1..R with rp[k] <= p
+#pragma unroll
+            for (int k = 1; k <= R; ++k) row += (p >= rp[k]) ? 1 : 0;
+            float v[NB];
+            const float val = ok ? half_bits_to_float(vb[u]) : 0.f;
+#pragma unroll
+            for (int t = 0; t < NB; ++t) v[t] = t < bn ? val * half_bits_to_float(xb[u][t]) : 0.f;
+            // segmented inclusive scan (rows are non-decreasing with the lane index)
+#define SQ_SEG_STEP(CTRL, MASK)                                                        \
+            {                                                                          \
+                const int r_up = dpp_i<CTRL, MASK>(-1, row);                           \
+                _Pragma("unroll") for (int t = 0; t < NB; ++t) {                       \
+                    const float v_up = dpp_f<CTRL, MASK>(0.f, v[t]);                   \
+                    v[t] += (r_up == row) ? v_up : 0.f;                                \
+                }                                                                      \
+            }
+            SQ_SEG_STEP(kRowShr1, 0xF)
+            SQ_SEG_STEP(kRowShr2, 0xF)
+            SQ_SEG_STEP(kRowShr4, 0xF)
+            SQ_SEG_STEP(kRowShr8, 0xF)
+            SQ_SEG_STEP(kRowBcast15, 0xA)
+            SQ_SEG_STEP(kRowBcast31, 0xC)
+#undef SQ_SEG_STEP
+            const int row_next = dpp_i<kWaveShl1>(-2, row);
+            if (ok && row_next != row) {                            // last lane of its row segment (row < R here)
+#pragma unroll
+                for (int t = 0; t < NB; ++t) sacc[row * NB + t] += v[t];
+            }
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------- the matvec kernel
-// grid.x = ceil(M / rows_per_wg); block = W * 64 threads, W = ceil(N / 2048) when dense, any W when sparse only.
-// dynamic LDS: float part[W][rows_per_wg][NB]  +  int srp[rows_per_wg + 1]
-template <int BITS, int NB, int RB>
+// grid.x = ceil(M / R); block = (W + S) * 64 threads: W = ceil(N / 2048) dense waves (0 if there is no dense
+// term), S = 1 sparse wave iff nnz > 0.  The dense path is straight-line code: out-of-range lanes and rows
+// load clamped (valid) addresses and are neutralised by zero activations / by not being stored.
+template <int BITS, int NB, int R, int D>
 __global__ void __launch_bounds__(1024) matvec_kernel(MatvecArgs g) {
-    extern __shared__ __align__(16) unsigned char lds_raw[];
+    static_assert(D >= 2 && D <= R, "prefetch depth");
+    constexpr int E = TableShape<BITS>::kEntries, K = 1 << BITS;
+    constexpr int kRawLanes = R * TableShape<BITS>::kRowBytes / 16;  // lanes that fetch 16 bytes of fp16 tables
+    __shared__ u32 tables[R * E];
+    __shared__ __align__(16) uint16_t raw[R * K];
+    __shared__ float part[kMaxDenseWaves * 4 * R * NB];              // [wave][16-lane row][r][t]
+    __shared__ float sacc[R * NB];
+
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int W = blockDim.x >> 6, T = blockDim.x;
-    const int rows = g.rows_per_wg;
-    const int r0 = blockIdx.x * rows;
-    const int nrows = min(rows, g.M - r0);
-    float* part = reinterpret_cast<float*>(lds_raw);                       // [W][rows][NB]
-    int* srp = reinterpret_cast<int*>(part + (size_t)W * rows * NB);       // [rows + 1]
-    const int B = g.B, bn = g.bn;                                         // x, y row stride; live batch columns
+    const bool dense = g.qidx != nullptr, sparse = g.nnz > 0;
+    const int W = dense ? (g.N + kSliceCols - 1) / kSliceCols : 0;
+    const int r0 = blockIdx.x * R;
+    const int nrows = min(R, g.M - r0);
+    const int B = g.B, bn = g.bn;
     const uint16_t* __restrict__ x = static_cast<const uint16_t*>(g.x) + g.bt0;
 
-    const bool sparse = g.nnz > 0;
-    if (sparse)
-        for (int k = tid; k <= nrows; k += T) srp[k] = g.rowptr[r0 + k];
-
-    // ---- dense term: this wave's 2048-column slice of every row of the block
-    if (g.qidx != nullptr) {
+    if (wave < W) {
+        // ---- dense wave.  Issue order: (wave 0: fp16 tables), activations, index stream of all R rows.
+        u32x4 rawv = {0, 0, 0, 0};
+        if (wave == 0 && lane < kRawLanes) {
+            const int u = lane * 16 / TableShape<BITS>::kRowBytes;
+            const int row = min(r0 + u, g.M - 1);
+            const char* src = static_cast<const char*>(g.lut) + (size_t)row * TableShape<BITS>::kRowBytes + (lane * 16) % TableShape<BITS>::kRowBytes;
+            rawv = *reinterpret_cast<const u32x4*>(src);
+        }
         const int j0 = wave * kSliceCols + lane * kLaneElems;
         const bool live = j0 < g.N;
+        const int j0c = live ? j0 : g.N - kLaneElems;
         u32 xr[NB][16];
-        load_x<NB>(x, B, bn, j0, live, xr);
+        load_x<NB>(x, B, bn, j0c, xr);
         const size_t row_dwords = (size_t)g.N * BITS / 32;
-        const u32* __restrict__ qbase = static_cast<const u32*>(g.qidx) + (size_t)r0 * row_dwords + (size_t)(j0 / 32) * BITS;
-        const uint16_t* __restrict__ lbase = static_cast<const uint16_t*>(g.lut) + (size_t)r0 * (1 << BITS);
-        for (int rb = 0; rb < nrows; rb += RB) {
-            LaneChunk<BITS> c[RB];
-            u32 table[RB];
+        const u32* __restrict__ qlane = static_cast<const u32*>(g.qidx) + (size_t)(j0c / 32) * BITS;
+        // index stream: D rows in flight; row u + D is requested when row u has been handed to the look-ups,
+        // so the requests of the block's waves interleave and every wave keeps receiving data
+        LaneChunk<BITS> c[R];
 #pragma unroll
-            for (int u = 0; u < RB; ++u) {
-                const bool ok = rb + u < nrows;                              // uniform
-                c[u] = load_chunk<BITS>(qbase + (size_t)(rb + u) * row_dwords, live && ok);
-                table[u] = ok ? load_table<BITS>(lbase + (size_t)(rb + u) * (1 << BITS), lane) : 0u;
+        for (int u = 0; u < D; ++u) c[u] = load_chunk<BITS>(qlane + (size_t)min(r0 + u, g.M - 1) * row_dwords);
+        if (!live) {
+#pragma unroll
+            for (int t = 0; t < NB; ++t)
+#pragma unroll
+                for (int p = 0; p < 16; ++p) xr[t][p] = 0;
+        }
+        if (wave == 0) {
+            if (lane < kRawLanes) *reinterpret_cast<u32x4*>(raw + lane * 8) = rawv;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            build_tables<BITS, R>(tables, raw, lane);
+        }
+        __syncthreads();
+        // software pipeline: the look-ups of row u + 1 are in flight while the products of row u are formed
+        float acc[NB][R];
+        u32 w[2][16];
+        lookup_chunk<BITS>(c[0], tables, w[0]);
+        if (D < R) c[D] = load_chunk<BITS>(qlane + (size_t)min(r0 + D, g.M - 1) * row_dwords);
+#pragma unroll
+        for (int u = 0; u < R; ++u) {
+            if (u + 1 < R) {
+                lookup_chunk<BITS>(c[u + 1], tables + (u + 1) * E, w[(u + 1) & 1]);
+                if (u + 1 + D < R) c[u + 1 + D] = load_chunk<BITS>(qlane + (size_t)min(r0 + u + 1 + D, g.M - 1) * row_dwords);
             }
+            __builtin_amdgcn_sched_barrier(0);
+            float a[NB];
+            dot_chunk<NB>(w[u & 1], xr, a);
 #pragma unroll
-            for (int u = 0; u < RB; ++u) {
-                float acc[NB];
+            for (int t = 0; t < NB; ++t) acc[t][u] = a[t];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // reduce the R row sums jointly: afterwards lane l holds row (l mod R) summed over its 16-lane row
 #pragma unroll
-                for (int t = 0; t < NB; ++t) acc[t] = 0.f;
-                accumulate_any<BITS, NB>(c[u], table[u], xr, acc);
-#pragma unroll
-                for (int t = 0; t < NB; ++t) {
-                    const float s = wave_sum(acc[t]);
-                    if (lane == 0 && rb + u < nrows) part[((size_t)wave * rows + rb + u) * NB + t] = s;
-                }
-            }
+        for (int t = 0; t < NB; ++t) {
+            row_block_reduce<R>(acc[t], lane);
+            if ((lane & 15) < R) part[((wave * 4 + (lane >> 4)) * R + (lane & 15)) * NB + t] = acc[t][0];
         }
     } else {
-        for (int k = lane; k < nrows * NB; k += kWave) part[(size_t)wave * rows * NB + k] = 0.f;
+        // ---- sparse wave (wave == W, present iff nnz > 0)
+        int rp[R + 1];
+#pragma unroll
+        for (int k = 0; k <= R; ++k) rp[k] = sparse ? g.rowptr[r0 + min(k, nrows)] : 0;   // uniform addresses
+        if (lane < R * NB) sacc[lane] = 0.f;
+        __syncthreads();
+        if (sparse) sparse_rows<NB, R>(g, x, lane, rp, sacc);
     }
     __syncthreads();
 
-    // ---- sparse term: nonzeros [P0, P1) of the block's rows, dealt out evenly to the T threads
-    if (sparse) {
-        const int P0 = srp[0], P1 = srp[nrows];
-        const int* __restrict__ cols = g.cols;
-        const uint16_t* __restrict__ vals = static_cast<const uint16_t*>(g.vals);
-        float* mine = part + (size_t)wave * rows * NB;
-        for (int pbase = P0 + wave * kWave; pbase < P1; pbase += T) {       // uniform per wave
-            const int p = pbase + lane;
-            const bool ok = p < P1;
-            int r = nrows;                                                   // sentinel row for idle lanes
-            float prod[NB];
-#pragma unroll
-            for (int t = 0; t < NB; ++t) prod[t] = 0.f;
-            if (ok) {
-                const int c = cols[p];
-                const float v = (float)__builtin_bit_cast(half_t, vals[p]);
-                int lo = 0, hi = nrows;                                      // largest r with srp[r] <= p
-                while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (srp[mid] <= p) lo = mid; else hi = mid; }
-                r = lo;
-#pragma unroll
-                for (int t = 0; t < NB; ++t)
-                    if (t < bn) prod[t] = v * (float)__builtin_bit_cast(half_t, x[(size_t)c * B + t]);
-            }
-            // segmented inclusive scan over lanes (rows are non-decreasing with the lane index)
-#pragma unroll
-            for (int d = 1; d < kWave; d <<= 1) {
-                const int r_up = __shfl_up(r, d, kWave);
-#pragma unroll
-                for (int t = 0; t < NB; ++t) {
-                    const float v_up = __shfl_up(prod[t], d, kWave);
-                    if (lane >= d && r_up == r) prod[t] += v_up;
-                }
-            }
-            const int r_next = __shfl_down(r, 1, kWave);
-            const bool tail = ok && (lane == kWave - 1 || r_next != r);
-            if (tail) {
-#pragma unroll
-                for (int t = 0; t < NB; ++t) mine[(size_t)r * NB + t] += prod[t];
-            }
-        }
-        __syncthreads();
-    }
-
-    // ---- combine the W partial sums in a fixed order, round once
+    // combine the W slice sums and the sparse term in a fixed order, round once
     uint16_t* __restrict__ y = static_cast<uint16_t*>(g.y) + g.bt0;
-    for (int k = tid; k < nrows * NB; k += T) {
-        const int r = k / NB, t = k - r * NB;
-        if (t >= bn) continue;
-        float s = 0.f;
-        for (int w = 0; w < W; ++w) s += part[((size_t)w * rows + r) * NB + t];
-        const size_t o = (size_t)(r0 + r) * B + t;
-        if (g.accumulate) s += (float)__builtin_bit_cast(half_t, y[o]);
-        y[o] = __builtin_bit_cast(uint16_t, (half_t)s);
+    if (tid < nrows * NB) {
+        const int r = tid / NB, t = tid - r * NB;
+        if (t < bn) {
+            float s = 0.f;
+            for (int w = 0; w < 4 * W; ++w) s += part[(w * R + r) * NB + t];
+            if (sparse) s += sacc[r * NB + t];
+            const size_t o = (size_t)(r0 + r) * B + t;
+            if (g.accumulate) s += half_bits_to_float(y[o]);
+            y[o] = float_to_half_bits(s);
+        }
     }
 }
 
@@ -305,10 +410,10 @@ __global__ void __launch_bounds__(256) csr_rowwise_kernel(MatvecArgs g) {
     if (g.nnz > 0) {
         for (int p = g.rowptr[i]; p < g.rowptr[i + 1]; ++p) {
             const int c = g.cols[p];
-            const float v = (float)__builtin_bit_cast(half_t, vals[p]);
+            const float v = half_bits_to_float(vals[p]);
 #pragma unroll
             for (int t = 0; t < NB; ++t)
-                if (t < g.bn) acc[t] += v * (float)__builtin_bit_cast(half_t, x[(size_t)c * g.B + t]);
+                if (t < g.bn) acc[t] += v * half_bits_to_float(x[(size_t)c * g.B + t]);
         }
     }
 #pragma unroll
@@ -316,54 +421,48 @@ __global__ void __launch_bounds__(256) csr_rowwise_kernel(MatvecArgs g) {
         if (t >= g.bn) continue;
         const size_t o = (size_t)i * g.B + t;
         float s = acc[t];
-        if (g.accumulate) s += (float)__builtin_bit_cast(half_t, y[o]);
-        y[o] = __builtin_bit_cast(uint16_t, (half_t)s);
+        if (g.accumulate) s += half_bits_to_float(y[o]);
+        y[o] = float_to_half_bits(s);
     }
 }
 
 // ---------------------------------------------------------------------------------------------- parity exports
-// Same load + address arithmetic + gather as the matvec; one wave per (row, slice).
+// Same load, field extraction, table build and look-up as the matvec; one wave per (row, slice).
+// Without a table (lut == nullptr) the fp16 table is replaced by the bit patterns 0, 1, 2, ... so that the
+// look-up returns the indices themselves.
 template <int BITS>
 __global__ void __launch_bounds__(64) decode_kernel(int M, int N, const void* qidx, const void* lut, void* idx_out, void* w_out) {
+    constexpr int E = TableShape<BITS>::kEntries, K = 1 << BITS;
+    __shared__ u32 table[E];
+    __shared__ __align__(16) uint16_t raw[K];
     const int lane = threadIdx.x;
     const int row = blockIdx.y, slice = blockIdx.x;
     const int j0 = slice * kSliceCols + lane * kLaneElems;
     const bool live = j0 < N;
+    const int j0c = live ? j0 : N - kLaneElems;
     const size_t row_dwords = (size_t)N * BITS / 32;
-    const u32* p = static_cast<const u32*>(qidx) + (size_t)row * row_dwords + (size_t)(j0 / 32) * BITS;
-    const LaneChunk<BITS> c = load_chunk<BITS>(p, live);
-    u32 idx[32], wbits[32];
-    if constexpr (BITS == 3) {
-        u32 a[16];
-        pair_addresses(c, a);
-        // identity tables: gathering them returns the lane number the address selects = the 6-bit field
-        const u32 table = lut ? load_table<3>(static_cast<const uint16_t*>(lut) + (size_t)row * 8, lane) : 0u;
+    const u32* p = static_cast<const u32*>(qidx) + (size_t)row * row_dwords + (size_t)(j0c / 32) * BITS;
+    const LaneChunk<BITS> c = load_chunk<BITS>(p);
+    if (lane < K) raw[lane] = lut ? static_cast<const uint16_t*>(lut)[(size_t)row * K + lane] : (uint16_t)lane;
+    __syncthreads();
+    build_tables<BITS, 1>(table, raw, lane);
+    __syncthreads();
+    u32 a[16];
+    pair_offsets(c, a);
+    u32 w[16];
+    const char* tb = reinterpret_cast<const char*>(table);
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            const u32 field = lane_gather(a[k], (u32)lane);
-            idx[2 * k] = field & 7; idx[2 * k + 1] = field >> 3;
-            const u32 w = lane_gather(a[k], table);
-            wbits[2 * k] = w & 0xFFFF; wbits[2 * k + 1] = w >> 16;
-        }
-    } else {
-        const u32 table = lut ? load_table<4>(static_cast<const uint16_t*>(lut) + (size_t)row * 16, lane) : 0u;
-#pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            const u32 a = elem_address(c, k);
-            idx[k] = lane_gather(a, (u32)lane) & 15;
-            wbits[k] = lane_gather(a, table) & 0xFFFF;
-        }
-    }
+    for (int k = 0; k < 16; ++k) w[k] = *reinterpret_cast<const u32*>(tb + a[k]);
     if (!live) return;
     if (idx_out) {
         uint8_t* o = static_cast<uint8_t*>(idx_out) + (size_t)row * N + j0;
 #pragma unroll
-        for (int k = 0; k < 32; ++k) o[k] = (uint8_t)idx[k];
+        for (int k = 0; k < 16; ++k) { o[2 * k] = (uint8_t)(w[k] & 0xFF); o[2 * k + 1] = (uint8_t)(w[k] >> 16); }
     }
     if (w_out) {
-        uint16_t* o = static_cast<uint16_t*>(w_out) + (size_t)row * N + j0;
+        u32* o = reinterpret_cast<u32*>(static_cast<uint16_t*>(w_out) + (size_t)row * N + j0);
 #pragma unroll
-        for (int k = 0; k < 32; ++k) o[k] = (uint16_t)wbits[k];
+        for (int k = 0; k < 16; ++k) o[k] = w[k];
     }
 }
 
@@ -384,7 +483,7 @@ __global__ void __launch_bounds__(256) fp16_gemv_kernel(int M, int N, int B, con
     for (int j = lane * 8; j < N; j += kWave * 8) {
         u32 xr[NB][4];
         if (NB == 1) {
-            const uint4 v = *reinterpret_cast<const uint4*>(x + j);
+            const u32x4 v = *reinterpret_cast<const u32x4*>(x + j);
             xr[0][0] = v.x; xr[0][1] = v.y; xr[0][2] = v.z; xr[0][3] = v.w;
         } else {
 #pragma unroll
@@ -409,38 +508,60 @@ __global__ void __launch_bounds__(256) fp16_gemv_kernel(int M, int N, int B, con
     for (int u = 0; u < RB; ++u)
 #pragma unroll
         for (int t = 0; t < NB; ++t) {
-            const float s = wave_sum(acc[u][t]);
-            if (lane == 0 && row0 + u < M && t < B) y[(size_t)(row0 + u) * B + t] = __builtin_bit_cast(uint16_t, (half_t)s);
+            const float s = wave_sum_to_lane63(acc[u][t]);
+            if (lane == 63 && row0 + u < M && t < B) y[(size_t)(row0 + u) * B + t] = float_to_half_bits(s);
         }
 }
 
 // ---------------------------------------------------------------------------------------------- launchers
-template <int BITS, int NB>
-static hipError_t launch_matvec_t(const MatvecArgs& g, int waves, hipStream_t s) {
-    constexpr int RB = (NB == 1) ? 4 : (NB == 2 ? 2 : 1);
-    const int grid = (g.M + g.rows_per_wg - 1) / g.rows_per_wg;
-    const size_t lds = (size_t)waves * g.rows_per_wg * NB * sizeof(float) + (size_t)(g.rows_per_wg + 1) * sizeof(int);
-    hipLaunchKernelGGL((matvec_kernel<BITS, NB, RB>), dim3(grid), dim3(waves * kWave), lds, s, g);
+template <int BITS, int NB, int R, int D>
+static hipError_t launch_matvec_r(const MatvecArgs& g, hipStream_t s) {
+    const int W = g.qidx ? (g.N + kSliceCols - 1) / kSliceCols : 0;
+    const int waves = W + (g.nnz > 0 ? 1 : 0);
+    const int grid = (g.M + R - 1) / R;
+    hipLaunchKernelGGL((matvec_kernel<BITS, NB, R, D>), dim3(grid), dim3(max(waves, 1) * kWave), 0, s, g);
     return hipGetLastError();
 }
 
+template <int BITS, int NB>
+static hipError_t launch_matvec_t(const MatvecArgs& g, hipStream_t s) {
+    // rows per workgroup: the activations of NB batch columns and the index stream in flight share the registers
+    if constexpr (NB == 4) {
+        return launch_matvec_r<BITS, NB, 4, 2>(g, s);
+    } else if constexpr (NB == 2) {
+        return g.rows_per_wg <= 4 ? launch_matvec_r<BITS, NB, 4, 2>(g, s) : launch_matvec_r<BITS, NB, 8, 2>(g, s);
+    } else {
+        const int d = g.prefetch_rows;
+        if (g.rows_per_wg <= 2) return launch_matvec_r<BITS, NB, 2, 2>(g, s);
+        if (g.rows_per_wg <= 4) return d <= 2 ? launch_matvec_r<BITS, NB, 4, 2>(g, s) : launch_matvec_r<BITS, NB, 4, 4>(g, s);
+        if (g.rows_per_wg <= 8) {
+            if (d <= 2) return launch_matvec_r<BITS, NB, 8, 2>(g, s);
+            if (d <= 4) return launch_matvec_r<BITS, NB, 8, 4>(g, s);
+            return launch_matvec_r<BITS, NB, 8, 8>(g, s);
+        }
+        if (d <= 2) return launch_matvec_r<BITS, NB, 16, 2>(g, s);
+        if (d <= 4) return launch_matvec_r<BITS, NB, 16, 4>(g, s);
+        return launch_matvec_r<BITS, NB, 16, 8>(g, s);
+    }
+}
+
 template <int BITS>
-static hipError_t launch_matvec_b(const MatvecArgs& g0, int waves, hipStream_t s) {
+static hipError_t launch_matvec_b(const MatvecArgs& g0, hipStream_t s) {
     // at most four batch columns per launch (their activations must fit in registers)
     for (int t0 = 0; t0 < g0.B; t0 += 4) {
         MatvecArgs g = g0;
         g.bt0 = t0; g.bn = min(4, g0.B - t0);
         hipError_t e;
-        if (g.bn == 1) e = launch_matvec_t<BITS, 1>(g, waves, s);
-        else if (g.bn == 2) e = launch_matvec_t<BITS, 2>(g, waves, s);
-        else e = launch_matvec_t<BITS, 4>(g, waves, s);
+        if (g.bn == 1) e = launch_matvec_t<BITS, 1>(g, s);
+        else if (g.bn == 2) e = launch_matvec_t<BITS, 2>(g, s);
+        else e = launch_matvec_t<BITS, 4>(g, s);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
-hipError_t launch_matvec(const MatvecArgs& g, int waves, hipStream_t s) {
-    return g.bits == 3 ? launch_matvec_b<3>(g, waves, s) : launch_matvec_b<4>(g, waves, s);
+hipError_t launch_matvec(const MatvecArgs& g, hipStream_t s) {
+    return g.bits == 3 ? launch_matvec_b<3>(g, s) : launch_matvec_b<4>(g, s);
 }
 
 hipError_t launch_csr_rowwise(const MatvecArgs& g0, hipStream_t s) {
