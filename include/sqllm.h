@@ -61,7 +61,7 @@ typedef enum {
 } sqllm_status;
 
 #define SQLLM_MAX_BATCH 8
-#define SQLLM_MAX_N 30720 /* widest row a workgroup covers with one 2048-column slice per wave (15 waves) */
+#define SQLLM_MAX_N 28672 /* widest row a workgroup covers with one 2048-column slice per wave (14 waves) */
 
 /* Dense term only (Sec. 4.3, the LUT-based matrix-vector kernel):
  *   accumulate == 0:  y = D x          accumulate != 0:  y = fp16( fp32(y) + D x )                        */
@@ -104,12 +104,8 @@ int sqllm_fp16_gemv(int M, int N, int B, const void* w, const void* x, void* y, 
 long long sqllm_algorithmic_bytes(int M, int N, int bits, long long nnz, int B);
 
 /* Tuning knob: rows handled by one workgroup of the matvec kernels (0 = library default; other values are
- * rounded up to 4, 8 or 16).  Affects speed only.  Returns the previous value.  Process-wide, not thread-safe. */
+ * rounded up to 2, 4, 8 or 16).  Affects speed only.  Returns the previous value.  Process-wide, not thread-safe. */
 int sqllm_set_rows_per_workgroup(int rows);
-
-/* Tuning knob: rows of the index stream each wave keeps in flight (0 = library default; rounded to 2, 4 or
- * 8 and capped by the rows per workgroup).  Affects speed only.  Returns the previous value.             */
-int sqllm_set_prefetch_rows(int rows);
 
 const char* sqllm_last_error_string(void); /* host pointer, valid until the thread's next failing call */
 const char* sqllm_status_string(int status);

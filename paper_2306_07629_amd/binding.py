@@ -16,7 +16,7 @@ STATUS_NAMES = ["SQLLM_OK", "SQLLM_ERR_NULL", "SQLLM_ERR_BITS", "SQLLM_ERR_SHAPE
 
 EXPORTS = ["sqllm_lut_gemv", "sqllm_csr_spmv", "sqllm_dense_sparse_matvec", "sqllm_csr_spmv_rowwise",
            "sqllm_unpack_indices", "sqllm_dequantize", "sqllm_fp16_gemv", "sqllm_algorithmic_bytes",
-           "sqllm_set_rows_per_workgroup", "sqllm_set_prefetch_rows", "sqllm_last_error_string", "sqllm_status_string", "sqllm_version"]
+           "sqllm_set_rows_per_workgroup", "sqllm_last_error_string", "sqllm_status_string", "sqllm_version"]
 
 
 class SqllmError(RuntimeError):
@@ -43,7 +43,6 @@ def lib() -> ctypes.CDLL:
         L.sqllm_algorithmic_bytes.argtypes = [i32, i32, i32, i64, i32]
         L.sqllm_algorithmic_bytes.restype = i64
         L.sqllm_set_rows_per_workgroup.argtypes = [i32]
-        L.sqllm_set_prefetch_rows.argtypes = [i32]
         L.sqllm_last_error_string.restype = ctypes.c_char_p
         L.sqllm_status_string.argtypes = [i32]
         L.sqllm_status_string.restype = ctypes.c_char_p
@@ -112,10 +111,6 @@ def sqllm_algorithmic_bytes(M, N, bits, nnz, B) -> int:
 
 def sqllm_set_rows_per_workgroup(rows: int) -> int:
     return int(lib().sqllm_set_rows_per_workgroup(int(rows)))
-
-
-def sqllm_set_prefetch_rows(rows: int) -> int:
-    return int(lib().sqllm_set_prefetch_rows(int(rows)))
 
 
 def sqllm_version() -> int:

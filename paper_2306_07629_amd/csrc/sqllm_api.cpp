@@ -13,7 +13,6 @@ namespace {
 
 thread_local char g_err[256] = "no error";
 int g_rows_per_wg = 0;   // 0 = choose per shape
-int g_prefetch_rows = 0;  // 0 = library default
 
 int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 int fail(int status, const char* fmt, ...) {
@@ -84,7 +83,6 @@ int run_matvec(int M, int N, int bits, long long nnz, int B, const void* qidx, c
     g.qidx = qidx; g.lut = lut; g.rowptr = rowptr; g.cols = cols; g.vals = vals; g.x = x; g.y = y;
     const int waves = qidx ? (N + 2047) / 2048 : 0;
     g.rows_per_wg = pick_rows(M, waves);
-    g.prefetch_rows = g_prefetch_rows > 0 ? g_prefetch_rows : 4;
     const hipError_t e = sqllm::launch_matvec(g, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "matvec launch");
     return SQLLM_OK;
@@ -175,12 +173,6 @@ long long sqllm_algorithmic_bytes(int M, int N, int bits, long long nnz, int B) 
 int sqllm_set_rows_per_workgroup(int rows) {
     const int old = g_rows_per_wg;
     g_rows_per_wg = rows < 0 ? 0 : (rows > 64 ? 64 : rows);
-    return old;
-}
-
-int sqllm_set_prefetch_rows(int rows) {
-    const int old = g_prefetch_rows;
-    g_prefetch_rows = rows < 0 ? 0 : (rows > 16 ? 16 : rows);
     return old;
 }
 

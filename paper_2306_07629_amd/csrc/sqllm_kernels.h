@@ -7,8 +7,7 @@ namespace sqllm {
 struct MatvecArgs {
     int M, N, bits, B;
     int bt0, bn;            // batch columns [bt0, bt0 + bn) are computed by this launch (bn <= 4)
-    int rows_per_wg;        // requested rows per workgroup; the launcher rounds it to 4, 8 or 16
-    int prefetch_rows;      // index-stream rows in flight per wave (rounded to 2, 4 or 8)
+    int rows_per_wg;        // requested rows per workgroup; the launcher rounds it to 2, 4, 8 or 16
     int accumulate;
     long long nnz;
     const void* qidx;       // nullptr -> no dense term
@@ -18,6 +17,9 @@ struct MatvecArgs {
     const void* vals;
     const void* x;
     void* y;
+#ifdef SQLLM_TRACE
+    unsigned long long* trace;   // per (block, wave) cycle stamps; stand-alone timing harness only
+#endif
 };
 
 hipError_t launch_matvec(const MatvecArgs& g, hipStream_t s);

@@ -41,7 +41,7 @@ typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kWave = 64;
 constexpr int kLaneElems = 32;                      // indices per lane per row
 constexpr int kSliceCols = kWave * kLaneElems;      // 2048 columns per wave
-constexpr int kMaxDenseWaves = 15;                  // N <= 30720
+constexpr int kMaxDenseWaves = 14;                  // N <= 28672 (two more waves of the block take the sparse term)
 
 // ---------------------------------------------------------------------------------------------- helpers
 __device__ __forceinline__ u32 funnel_shr(u32 hi, u32 lo, u32 sh) { return __builtin_amdgcn_alignbit(hi, lo, sh); }
@@ -136,6 +136,7 @@ __device__ __forceinline__ void build_tables(u32* __restrict__ tables, const uin
 
 // ---------------------------------------------------------------------------------------------- x in registers
 // xr[t][p] = (x[j0 + 2p][t], x[j0 + 2p + 1][t]) for the lane's 32 columns j0 .. j0 + 31 (j0 is in range).
+// x points at the first live batch column; B is the row stride of x, bn the number of live columns.
 template <int NB>
 __device__ __forceinline__ void load_x(const uint16_t* __restrict__ x, int B, int bn, int j0, u32 (&xr)[NB][16]) {
     if (NB == 1 && B == 1) {
@@ -145,17 +146,30 @@ __device__ __forceinline__ void load_x(const uint16_t* __restrict__ x, int B, in
             const u32x4 v = src[k];
             xr[0][4 * k + 0] = v.x; xr[0][4 * k + 1] = v.y; xr[0][4 * k + 2] = v.z; xr[0][4 * k + 3] = v.w;
         }
-    } else {
+    } else if (NB >= 2) {
+        // even row stride (the launcher guarantees it): a row's live columns are whole dwords (the column
+        // window starts at a multiple of 4 and holds 2 or 4 columns); pairs of rows are transposed with
+        // byte permutes
 #pragma unroll
-        for (int t = 0; t < NB; ++t) {
-            const int tc = t < bn ? t : 0;                          // clamp, zeroed below
+        for (int p = 0; p < 16; ++p) {
+            const u32* ra = reinterpret_cast<const u32*>(x + (size_t)(j0 + 2 * p) * B);
+            const u32* rb = reinterpret_cast<const u32*>(x + (size_t)(j0 + 2 * p + 1) * B);
 #pragma unroll
-            for (int p = 0; p < 16; ++p) {
-                const u32 lo = x[(size_t)(j0 + 2 * p) * B + tc], hi = x[(size_t)(j0 + 2 * p + 1) * B + tc];
-                xr[t][p] = t < bn ? (lo | (hi << 16)) : 0u;
+            for (int h = 0; h < NB / 2; ++h) {
+                const u32 a = ra[h], b = rb[h];
+                xr[2 * h][p] = __builtin_amdgcn_perm(b, a, 0x05040100u);       // (a.lo, b.lo)
+                xr[2 * h + 1][p] = __builtin_amdgcn_perm(b, a, 0x07060302u);   // (a.hi, b.hi)
             }
         }
+    } else {
+        // one column of a wider batch: one 16-bit load per value
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const u32 lo = x[(size_t)(j0 + 2 * p) * B], hi = x[(size_t)(j0 + 2 * p + 1) * B];
+            xr[0][p] = lo | (hi << 16);
+        }
     }
+    (void)bn;
 }
 
 // table look-ups of one row slice: 16 dwords, each an fp16 pair
@@ -227,82 +241,173 @@ __device__ __forceinline__ void row_block_reduce(float (&v)[C], int lane) {
     }
 }
 
-// ---------------------------------------------------------------------------------------------- sparse wave
-// Nonzeros [P0, P1) of rows r0 .. r0 + R - 1; rp[k] = rowptr[r0 + k] (uniform, rp[k] = P1 beyond the last row).
-// Lane l takes nonzeros P0 + l, P0 + l + 64, ...; UNR batches of 64 are loaded before the first is reduced.
-// Row sums are added into sacc[row * NB + t] by the last lane of each row segment.
-template <int NB, int R>
-__device__ __forceinline__ void sparse_rows(const MatvecArgs& g, const uint16_t* __restrict__ x, int lane, const int (&rp)[R + 1], float* __restrict__ sacc) {
-    const int P0 = rp[0], P1 = rp[R];
+// ---------------------------------------------------------------------------------------------- sparse term
+// Balanced CSR (cf. Sec. 4.3).  The nonzeros of the block's R rows are ONE contiguous range [P0, P1) of the
+// CSR arrays.  It is cut into batches of 64; batch b goes to wave (b mod NW) and lane l of that wave takes
+// nonzero P0 + 64 b + l, whatever row it falls in -- every lane of the block gets the same amount of work
+// and a heavy row is spread over all waves.  A wave handles up to UB batches per round: first all column /
+// value loads, then all activation gathers, then the reduction, so a round costs two memory round trips
+// (which the dense decode of the same wave overlaps).  Products are combined per row inside the wave (plain
+// DPP reduction when a batch lies in one row, segmented DPP scan otherwise) and only the last lane of a row
+// segment adds to the wave's private LDS slot of that row: no floating-point atomics, fixed summation order.
+template <int NB, int UB>
+struct SparseRegs {
+    int c[UB];
+    uint16_t vb[UB];
+    uint16_t xb[UB][NB];
+};
+
+struct SparseRange {
+    int P0, P1, nbatch;
+};
+
+// Loads of one round are unconditional (indices clamped into [P0, P1), surplus lanes and batches are masked
+// in the reduction), so that all of them are in flight at once.
+template <int NB, int UB>
+__device__ __forceinline__ void sparse_issue_cols_vals(const MatvecArgs& g, const SparseRange& sr, int b0, int NW, int lane, SparseRegs<NB, UB>& q) {
     const int* __restrict__ cols = g.cols;
     const uint16_t* __restrict__ vals = static_cast<const uint16_t*>(g.vals);
-    const int B = g.B, bn = g.bn;
-    constexpr int UNR = NB == 1 ? 8 : (NB == 2 ? 4 : 2);
-    for (int pb = P0; pb < P1; pb += UNR * kWave) {                // uniform
-        int c[UNR]; uint16_t vb[UNR];
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const int p = min(pb + u * kWave + lane, P1 - 1);       // clamped, masked below
-            c[u] = cols[p];
-            vb[u] = vals[p];
-        }
-        uint16_t xb[UNR][NB];
-#pragma unroll
-        for (int u = 0; u < UNR; ++u)
-#pragma unroll
-            for (int t = 0; t < NB; ++t) xb[u][t] = x[(size_t)c[u] * B + (t < bn ? t : 0)];
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            if (pb + u * kWave >= P1) break;                       // uniform
-            const int p = pb + u * kWave + lane;
-            const bool ok = p < P1;
-            int row = 0;                                           // number of k in 1..R with rp[k] <= p
-#pragma unroll
-            for (int k = 1; k <= R; ++k) row += (p >= rp[k]) ? 1 : 0;
-            float v[NB];
-            const float val = ok ? half_bits_to_float(vb[u]) : 0.f;
-#pragma unroll
-            for (int t = 0; t < NB; ++t) v[t] = t < bn ? val * half_bits_to_float(xb[u][t]) : 0.f;
-            // segmented inclusive scan (rows are non-decreasing with the lane index)
-#define SQ_SEG_STEP(CTRL, MASK)                                                        \
-            {                                                                          \
-                const int r_up = dpp_i<CTRL, MASK>(-1, row);                           \
-                _Pragma("unroll") for (int t = 0; t < NB; ++t) {                       \
-                    const float v_up = dpp_f<CTRL, MASK>(0.f, v[t]);                   \
-                    v[t] += (r_up == row) ? v_up : 0.f;                                \
-                }                                                                      \
-            }
-            SQ_SEG_STEP(kRowShr1, 0xF)
-            SQ_SEG_STEP(kRowShr2, 0xF)
-            SQ_SEG_STEP(kRowShr4, 0xF)
-            SQ_SEG_STEP(kRowShr8, 0xF)
-            SQ_SEG_STEP(kRowBcast15, 0xA)
-            SQ_SEG_STEP(kRowBcast31, 0xC)
-#undef SQ_SEG_STEP
-            const int row_next = dpp_i<kWaveShl1>(-2, row);
-            if (ok && row_next != row) {                            // last lane of its row segment (row < R here)
-#pragma unroll
-                for (int t = 0; t < NB; ++t) sacc[row * NB + t] += v[t];
-            }
-        }
+    for (int k = 0; k < UB; ++k) {
+        const int p = min(sr.P0 + (b0 + k * NW) * kWave + lane, sr.P1 - 1);
+        q.c[k] = cols[p];
+        q.vb[k] = vals[p];
     }
 }
 
+template <int NB, int UB>
+__device__ __forceinline__ void sparse_issue_gathers(const MatvecArgs& g, const uint16_t* __restrict__ x, SparseRegs<NB, UB>& q) {
+#pragma unroll
+    for (int k = 0; k < UB; ++k)
+#pragma unroll
+        for (int t = 0; t < NB; ++t) q.xb[k][t] = x[(size_t)q.c[k] * g.B + t];
+}
+
+// LDS float add without a returned value: queued in order behind the wave's earlier LDS operations.  Only one
+// wave ever touches a given slot and its lanes address distinct slots, so the summation order is fixed.
+__device__ __forceinline__ void lds_add(float* slot, float v) { (void)__hip_atomic_fetch_add(slot, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+
+template <int NB, int R, int UB>
+__device__ __forceinline__ void sparse_reduce(const SparseRange& sr, const int (&rp)[R + 1], int b0, int NW, int lane, const SparseRegs<NB, UB>& q, float* __restrict__ slots) {
+    int carry_row = -1;                                              // uniform: row whose sum is still in registers
+    float carry[NB];
+#pragma unroll
+    for (int t = 0; t < NB; ++t) carry[t] = 0.f;
+#pragma unroll
+    for (int k = 0; k < UB; ++k) {
+        const int b = b0 + k * NW;
+        if (b < sr.nbatch) {                                         // uniform
+            const int p_first = sr.P0 + b * kWave, p_last = min(p_first + kWave, sr.P1) - 1;
+            const int p = p_first + lane;
+            const bool ok = p <= p_last;
+            float v[NB];
+#pragma unroll
+            for (int t = 0; t < NB; ++t) v[t] = ok ? half_bits_to_float(q.vb[k]) * half_bits_to_float(q.xb[k][t]) : 0.f;
+            int row_first = 0, row_last = 0;                         // rows of the batch's first / last nonzero
+#pragma unroll
+            for (int i = 1; i < R; ++i) { row_first += (p_first >= rp[i]) ? 1 : 0; row_last += (p_last >= rp[i]) ? 1 : 0; }
+            if (row_first == row_last) {
+                // the whole batch lies in one row: plain wave reduction, summed in registers across batches
+                if (carry_row != row_first) {
+                    if (carry_row >= 0 && lane == kWave - 1) {
+#pragma unroll
+                        for (int t = 0; t < NB; ++t) lds_add(slots + carry_row * NB + t, carry[t]);
+                    }
+                    carry_row = row_first;
+#pragma unroll
+                    for (int t = 0; t < NB; ++t) carry[t] = 0.f;
+                }
+#pragma unroll
+                for (int t = 0; t < NB; ++t) carry[t] += wave_sum_to_lane63(v[t]);
+            } else {
+                int row = 0;                                         // number of i in 1..R-1 with rp[i] <= p
+#pragma unroll
+                for (int i = 1; i < R; ++i) row += (p >= rp[i]) ? 1 : 0;
+                if (!ok) row = R;                                    // idle lanes form their own segment
+                // segmented inclusive scan (rows are non-decreasing with the lane index)
+#define SQ_SEG_STEP(CTRL, MASK)                                                        \
+                {                                                                      \
+                    const int r_up = dpp_i<CTRL, MASK>(-1, row);                       \
+                    _Pragma("unroll") for (int t = 0; t < NB; ++t) {                   \
+                        const float v_up = dpp_f<CTRL, MASK>(0.f, v[t]);               \
+                        v[t] += (r_up == row) ? v_up : 0.f;                            \
+                    }                                                                  \
+                }
+                SQ_SEG_STEP(kRowShr1, 0xF)
+                SQ_SEG_STEP(kRowShr2, 0xF)
+                SQ_SEG_STEP(kRowShr4, 0xF)
+                SQ_SEG_STEP(kRowShr8, 0xF)
+                SQ_SEG_STEP(kRowBcast15, 0xA)
+                SQ_SEG_STEP(kRowBcast31, 0xC)
+#undef SQ_SEG_STEP
+                const int row_next = dpp_i<kWaveShl1>(-2, row);
+                if (ok && row_next != row) {                          // last lane of its row segment
+#pragma unroll
+                    for (int t = 0; t < NB; ++t) lds_add(slots + row * NB + t, v[t]);
+                }
+            }
+        }
+    }
+    if (carry_row >= 0 && lane == kWave - 1) {
+#pragma unroll
+        for (int t = 0; t < NB; ++t) lds_add(slots + carry_row * NB + t, carry[t]);
+    }
+}
+
+#ifdef SQLLM_TRACE
+#define SQ_TRACE(slot) do { if (g.trace && lane == 0) g.trace[((size_t)blockIdx.x * 32 + (threadIdx.x >> 6)) * 8 + (slot)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define SQ_TRACE(slot) do { } while (0)
+#endif
+
+template <int NB, int R, int U>
+__device__ __forceinline__ void sparse_round(const MatvecArgs& g, const uint16_t* __restrict__ x, const SparseRange& sr, const int (&rp)[R + 1],
+                                             int b0, int NW, int lane, float* __restrict__ slots) {
+    SparseRegs<NB, U> q;
+    sparse_issue_cols_vals<NB, U>(g, sr, b0, NW, lane, q);
+#ifdef SQLLM_TRACE
+    { int acc = 0; for (int k = 0; k < U; ++k) acc += q.c[k] + q.vb[k]; if (acc == 0x7fffffff) slots[0] = 1.f; }   // wait for the loads
+    SQ_TRACE(2);
+#endif
+    sparse_issue_gathers<NB, U>(g, x, q);
+#ifdef SQLLM_TRACE
+    { int acc = 0; for (int k = 0; k < U; ++k) acc += q.xb[k][0]; if (acc == 0x7fffffff) slots[0] = 1.f; }
+    SQ_TRACE(3);
+#endif
+    sparse_reduce<NB, R, U>(sr, rp, b0, NW, lane, q, slots);
+    SQ_TRACE(4);
+}
+
 // ---------------------------------------------------------------------------------------------- the matvec kernel
-// grid.x = ceil(M / R); block = (W + S) * 64 threads: W = ceil(N / 2048) dense waves (0 if there is no dense
-// term), S = 1 sparse wave iff nnz > 0.  The dense path is straight-line code: out-of-range lanes and rows
-// load clamped (valid) addresses and are neutralised by zero activations / by not being stored.
-template <int BITS, int NB, int R, int D>
-__global__ void __launch_bounds__(1024) matvec_kernel(MatvecArgs g) {
+// grid.x = ceil(M / R); block = (W + S) waves.  W = ceil(N / 2048) dense waves (0 without a dense term), wave w
+// owning column slice w; S sparse waves (1 next to a dense term, kSparseOnlyWaves alone, 0 when nnz == 0).
+// The sparse wave works through the first UB batches of the block's nonzeros while the dense waves stream
+// (that is all of them except in blocks holding a very heavy row); whatever is left is dealt out to ALL
+// waves once the dense waves have finished their rows, so a heavy row never serialises on one wave.
+// The dense path is straight-line code: out-of-range lanes and rows load clamped (valid) addresses and are
+// neutralised by zero activations / by not being stored.
+constexpr int kSparseOnlyWaves = 4;
+
+template <int NB, int R>
+__device__ __forceinline__ void load_row_pointers(const MatvecArgs& g, int r0, int nrows, bool sparse, int (&rp)[R + 1], SparseRange& sr) {
+#pragma unroll
+    for (int k = 0; k <= R; ++k) rp[k] = sparse ? g.rowptr[r0 + min(k, nrows)] : 0;   // uniform -> scalar loads
+    sr.P0 = rp[0]; sr.P1 = rp[R]; sr.nbatch = (sr.P1 - sr.P0 + kWave - 1) / kWave;
+}
+
+template <int BITS, int NB, int R, int D, int MAXT>
+__global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
     static_assert(D >= 2 && D <= R, "prefetch depth");
     constexpr int E = TableShape<BITS>::kEntries, K = 1 << BITS;
     constexpr int kRawLanes = R * TableShape<BITS>::kRowBytes / 16;  // lanes that fetch 16 bytes of fp16 tables
+    constexpr int UB = NB == 1 ? 8 : (NB == 2 ? 4 : 2);              // sparse batches per wave and round
     __shared__ u32 tables[R * E];
     __shared__ __align__(16) uint16_t raw[R * K];
-    __shared__ float part[kMaxDenseWaves * 4 * R * NB];              // [wave][16-lane row][r][t]
-    __shared__ float sacc[R * NB];
+    __shared__ float part[kMaxDenseWaves * 4 * R * NB];              // dense:  [wave][16-lane row][r][t]
+    __shared__ float spart[(kMaxDenseWaves + 1) * R * NB];           // sparse: [wave][r][t]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int NW = blockDim.x >> 6;
     const bool dense = g.qidx != nullptr, sparse = g.nnz > 0;
     const int W = dense ? (g.N + kSliceCols - 1) / kSliceCols : 0;
     const int r0 = blockIdx.x * R;
@@ -310,8 +415,16 @@ __global__ void __launch_bounds__(1024) matvec_kernel(MatvecArgs g) {
     const int B = g.B, bn = g.bn;
     const uint16_t* __restrict__ x = static_cast<const uint16_t*>(g.x) + g.bt0;
 
+    int rp[R + 1];
+    SparseRange sr;
+    load_row_pointers<NB, R>(g, r0, nrows, sparse, rp, sr);          // consumed late by the dense waves
+    float* myslots = spart + wave * R * NB;
+    if (lane < R * NB) myslots[lane] = 0.f;
+    int next_batch = 0;                                              // first batch not yet handled (uniform)
+
     if (wave < W) {
-        // ---- dense wave.  Issue order: (wave 0: fp16 tables), activations, index stream of all R rows.
+        SQ_TRACE(0);
+        // ---- dense wave.  Issue order: (wave 0: fp16 tables), activations, first D rows of the index stream.
         u32x4 rawv = {0, 0, 0, 0};
         if (wave == 0 && lane < kRawLanes) {
             const int u = lane * 16 / TableShape<BITS>::kRowBytes;
@@ -326,8 +439,6 @@ __global__ void __launch_bounds__(1024) matvec_kernel(MatvecArgs g) {
         load_x<NB>(x, B, bn, j0c, xr);
         const size_t row_dwords = (size_t)g.N * BITS / 32;
         const u32* __restrict__ qlane = static_cast<const u32*>(g.qidx) + (size_t)(j0c / 32) * BITS;
-        // index stream: D rows in flight; row u + D is requested when row u has been handed to the look-ups,
-        // so the requests of the block's waves interleave and every wave keeps receiving data
         LaneChunk<BITS> c[R];
 #pragma unroll
         for (int u = 0; u < D; ++u) c[u] = load_chunk<BITS>(qlane + (size_t)min(r0 + u, g.M - 1) * row_dwords);
@@ -345,16 +456,17 @@ __global__ void __launch_bounds__(1024) matvec_kernel(MatvecArgs g) {
             build_tables<BITS, R>(tables, raw, lane);
         }
         __syncthreads();
-        // software pipeline: the look-ups of row u + 1 are in flight while the products of row u are formed
+        // software pipeline: the look-ups of row u + 1 are in flight while the products of row u are formed;
+        // row u + D of the index stream is requested when row u has been handed to the look-ups
         float acc[NB][R];
         u32 w[2][16];
         lookup_chunk<BITS>(c[0], tables, w[0]);
-        if (D < R) c[D] = load_chunk<BITS>(qlane + (size_t)min(r0 + D, g.M - 1) * row_dwords);
+        if constexpr (D < R) c[D] = load_chunk<BITS>(qlane + (size_t)min(r0 + D, g.M - 1) * row_dwords);
 #pragma unroll
         for (int u = 0; u < R; ++u) {
             if (u + 1 < R) {
                 lookup_chunk<BITS>(c[u + 1], tables + (u + 1) * E, w[(u + 1) & 1]);
-                if (u + 1 + D < R) c[u + 1 + D] = load_chunk<BITS>(qlane + (size_t)min(r0 + u + 1 + D, g.M - 1) * row_dwords);
+                if (u + 1 + D < R) c[(u + 1 + D) % R] = load_chunk<BITS>(qlane + (size_t)min(r0 + u + 1 + D, g.M - 1) * row_dwords);
             }
             __builtin_amdgcn_sched_barrier(0);
             float a[NB];
@@ -369,25 +481,34 @@ __global__ void __launch_bounds__(1024) matvec_kernel(MatvecArgs g) {
             row_block_reduce<R>(acc[t], lane);
             if ((lane & 15) < R) part[((wave * 4 + (lane >> 4)) * R + (lane & 15)) * NB + t] = acc[t][0];
         }
+        next_batch = UB;                                             // the sparse wave takes batches 0 .. UB-1
     } else {
-        // ---- sparse wave (wave == W, present iff nnz > 0)
-        int rp[R + 1];
-#pragma unroll
-        for (int k = 0; k <= R; ++k) rp[k] = sparse ? g.rowptr[r0 + min(k, nrows)] : 0;   // uniform addresses
-        if (lane < R * NB) sacc[lane] = 0.f;
-        __syncthreads();
-        if (sparse) sparse_rows<NB, R>(g, x, lane, rp, sacc);
+        // ---- sparse wave(s)
+        SQ_TRACE(0);
+        if (dense) {
+            __syncthreads();                                          // the dense waves' table barrier
+            SQ_TRACE(1);
+            if (sr.nbatch > 2) sparse_round<NB, R, UB>(g, x, sr, rp, 0, 1, lane, myslots);
+            else if (sr.nbatch > 0) sparse_round<NB, R, 2>(g, x, sr, rp, 0, 1, lane, myslots);
+            next_batch = UB;
+        }
     }
+    // ---- what is left of the sparse term (everything in a sparse-only launch): batch b goes to wave
+    //      (b - next_batch) mod NW, UB batches per wave and round
+    for (int b0 = next_batch + wave; b0 < sr.nbatch; b0 += NW * UB)   // uniform
+        sparse_round<NB, R, UB>(g, x, sr, rp, b0, NW, lane, myslots);
+    SQ_TRACE(5);
     __syncthreads();
 
-    // combine the W slice sums and the sparse term in a fixed order, round once
+    // combine the slice sums and the sparse partial sums in a fixed order, round once
     uint16_t* __restrict__ y = static_cast<uint16_t*>(g.y) + g.bt0;
     if (tid < nrows * NB) {
         const int r = tid / NB, t = tid - r * NB;
         if (t < bn) {
             float s = 0.f;
             for (int w = 0; w < 4 * W; ++w) s += part[(w * R + r) * NB + t];
-            if (sparse) s += sacc[r * NB + t];
+            if (sparse)
+                for (int w = 0; w < NW; ++w) s += spart[(w * R + r) * NB + t];
             const size_t o = (size_t)(r0 + r) * B + t;
             if (g.accumulate) s += half_bits_to_float(y[o]);
             y[o] = float_to_half_bits(s);
@@ -517,9 +638,18 @@ __global__ void __launch_bounds__(256) fp16_gemv_kernel(int M, int N, int B, con
 template <int BITS, int NB, int R, int D>
 static hipError_t launch_matvec_r(const MatvecArgs& g, hipStream_t s) {
     const int W = g.qidx ? (g.N + kSliceCols - 1) / kSliceCols : 0;
-    const int waves = W + (g.nnz > 0 ? 1 : 0);
+    const int S = g.nnz > 0 ? (W ? 1 : kSparseOnlyWaves) : (W ? 0 : 1);
+    const int waves = W + S;
     const int grid = (g.M + R - 1) / R;
-    hipLaunchKernelGGL((matvec_kernel<BITS, NB, R, D>), dim3(grid), dim3(max(waves, 1) * kWave), 0, s, g);
+    // batched kernels hold 32 * NB activations per lane: give them the larger register budget of a block
+    // of at most 512 threads whenever the row is narrow enough
+    if constexpr (NB > 1) {
+        if (waves * kWave <= 512) {
+            hipLaunchKernelGGL((matvec_kernel<BITS, NB, R, D, 512>), dim3(grid), dim3(waves * kWave), 0, s, g);
+            return hipGetLastError();
+        }
+    }
+    hipLaunchKernelGGL((matvec_kernel<BITS, NB, R, D, 1024>), dim3(grid), dim3(waves * kWave), 0, s, g);
     return hipGetLastError();
 }
 
@@ -531,26 +661,22 @@ static hipError_t launch_matvec_t(const MatvecArgs& g, hipStream_t s) {
     } else if constexpr (NB == 2) {
         return g.rows_per_wg <= 4 ? launch_matvec_r<BITS, NB, 4, 2>(g, s) : launch_matvec_r<BITS, NB, 8, 2>(g, s);
     } else {
-        const int d = g.prefetch_rows;
         if (g.rows_per_wg <= 2) return launch_matvec_r<BITS, NB, 2, 2>(g, s);
-        if (g.rows_per_wg <= 4) return d <= 2 ? launch_matvec_r<BITS, NB, 4, 2>(g, s) : launch_matvec_r<BITS, NB, 4, 4>(g, s);
-        if (g.rows_per_wg <= 8) {
-            if (d <= 2) return launch_matvec_r<BITS, NB, 8, 2>(g, s);
-            if (d <= 4) return launch_matvec_r<BITS, NB, 8, 4>(g, s);
-            return launch_matvec_r<BITS, NB, 8, 8>(g, s);
-        }
-        if (d <= 2) return launch_matvec_r<BITS, NB, 16, 2>(g, s);
-        if (d <= 4) return launch_matvec_r<BITS, NB, 16, 4>(g, s);
-        return launch_matvec_r<BITS, NB, 16, 8>(g, s);
+        if (g.rows_per_wg <= 4) return launch_matvec_r<BITS, NB, 4, 4>(g, s);
+        if (g.rows_per_wg <= 8) return launch_matvec_r<BITS, NB, 8, 4>(g, s);
+        return launch_matvec_r<BITS, NB, 16, 4>(g, s);
     }
 }
 
 template <int BITS>
 static hipError_t launch_matvec_b(const MatvecArgs& g0, hipStream_t s) {
-    // at most four batch columns per launch (their activations must fit in registers)
-    for (int t0 = 0; t0 < g0.B; t0 += 4) {
+    // Batch columns are processed in windows: 4 (or 2) columns per launch when the batch is even -- their
+    // activations must fit in registers -- and one column per launch when it is odd (rows of x are then not
+    // dword aligned).  B = 1, 2 and 4 are single launches.
+    const int step = g0.B == 1 ? 1 : ((g0.B & 1) ? 1 : 4);
+    for (int t0 = 0; t0 < g0.B; t0 += step) {
         MatvecArgs g = g0;
-        g.bt0 = t0; g.bn = min(4, g0.B - t0);
+        g.bt0 = t0; g.bn = min(step, g0.B - t0);
         hipError_t e;
         if (g.bn == 1) e = launch_matvec_t<BITS, 1>(g, s);
         else if (g.bn == 2) e = launch_matvec_t<BITS, 2>(g, s);

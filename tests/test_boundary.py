@@ -47,7 +47,7 @@ def test_lut_gemv_argument_errors():
     expect("SQLLM_ERR_SHAPE", f, 4, 0, 3, 1, A, A, A, A)
     expect("SQLLM_ERR_SHAPE", f, 4, 100, 3, 1, A, A, A, A)
     expect("SQLLM_ERR_SHAPE", f, 4, 64, 4, 1, A, A, A, A)
-    expect("SQLLM_ERR_SHAPE", f, 4, 30720 + 128, 3, 1, A, A, A, A)
+    expect("SQLLM_ERR_SHAPE", f, 4, 28672 + 128, 3, 1, A, A, A, A)
     expect("SQLLM_ERR_BATCH", f, 4, 128, 3, 0, A, A, A, A)
     expect("SQLLM_ERR_BATCH", f, 4, 128, 3, 9, A, A, A, A)
     expect("SQLLM_ERR_NULL", f, 4, 128, 3, 1, None, A, A, A)
