@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rows-per-wg", type=int, default=0)
     ap.add_argument("--no-graph", action="store_true", help="issue every launch from Python instead of replaying a HIP graph")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy 20 times (reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -162,6 +164,14 @@ def main():
     us_f_torch = sec_f_torch / (fsteps * len(shapes)) * 1e6
     us_f = min(us_f_own, us_f_torch)
     del wring
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_()
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- HBM traffic per launch measured with rocprofv3 counters, if a summary is committed
     traffic = None
