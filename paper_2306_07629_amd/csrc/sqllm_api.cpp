@@ -64,13 +64,16 @@ int hip_fail(hipError_t e, const char* what) {
     return fail(SQLLM_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-// Rows handled by one workgroup (the kernels are built for 2, 4, 8 and 16).  Measured on MI355X at the
-// LLaMA-7B shapes: 4 rows is the fastest -- the whole matrix is requested within the first microsecond and
-// the time after the last byte arrives is the decode time of one workgroup, which grows with its row count.
+// Rows handled by one workgroup (the kernels are built for 2, 4, 8 and 16).  Measured on MI355X: when all
+// workgroups of the launch are resident at once (at most 8 waves on each of the 1024 SIMDs) 4 rows is the
+// fastest -- the whole matrix is requested within the first microsecond and the time after the last byte
+// arrives is the decode time of one workgroup, which grows with its row count.  Larger launches run in
+// several generations; there 8 rows keep the dense waves busy for as long as the sparse chain of the block
+// (row pointers -> columns / values -> gathers) takes, so the sparse wave does not hold the block's slot.
 int pick_rows(int M, int waves_per_wg) {
     if (g_rows_per_wg > 0) return g_rows_per_wg;
-    (void)M; (void)waves_per_wg;
-    return 4;
+    const long long resident_waves = 256ll * 4 * 8;
+    return ((long long)(M + 3) / 4) * waves_per_wg <= resident_waves ? 4 : 8;
 }
 
 int run_matvec(int M, int N, int bits, long long nnz, int B, const void* qidx, const void* lut, const int* rowptr,
@@ -81,7 +84,7 @@ int run_matvec(int M, int N, int bits, long long nnz, int B, const void* qidx, c
     g.M = M; g.N = N; g.bits = bits; g.B = B; g.bt0 = 0; g.bn = B;
     g.accumulate = accumulate; g.nnz = nnz;
     g.qidx = qidx; g.lut = lut; g.rowptr = rowptr; g.cols = cols; g.vals = vals; g.x = x; g.y = y;
-    const int waves = qidx ? (N + 2047) / 2048 : 0;
+    const int waves = qidx ? (N + 2047) / 2048 + (nnz > 0 ? 1 : 0) : 4;
     g.rows_per_wg = pick_rows(M, waves);
     const hipError_t e = sqllm::launch_matvec(g, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "matvec launch");

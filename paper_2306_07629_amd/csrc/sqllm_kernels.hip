@@ -147,20 +147,7 @@ __device__ __forceinline__ void load_x(const uint16_t* __restrict__ x, int B, in
             xr[0][4 * k + 0] = v.x; xr[0][4 * k + 1] = v.y; xr[0][4 * k + 2] = v.z; xr[0][4 * k + 3] = v.w;
         }
     } else if (NB >= 2) {
-        // even row stride (the launcher guarantees it): a row's live columns are whole dwords (the column
-        // window starts at a multiple of 4 and holds 2 or 4 columns); pairs of rows are transposed with
-        // byte permutes
-#pragma unroll
-        for (int p = 0; p < 16; ++p) {
-            const u32* ra = reinterpret_cast<const u32*>(x + (size_t)(j0 + 2 * p) * B);
-            const u32* rb = reinterpret_cast<const u32*>(x + (size_t)(j0 + 2 * p + 1) * B);
-#pragma unroll
-            for (int h = 0; h < NB / 2; ++h) {
-                const u32 a = ra[h], b = rb[h];
-                xr[2 * h][p] = __builtin_amdgcn_perm(b, a, 0x05040100u);       // (a.lo, b.lo)
-                xr[2 * h + 1][p] = __builtin_amdgcn_perm(b, a, 0x07060302u);   // (a.hi, b.hi)
-            }
-        }
+        // handled by load_x_staged (coalesced loads transposed through LDS)
     } else {
         // one column of a wider batch: one 16-bit load per value
 #pragma unroll
@@ -170,6 +157,65 @@ __device__ __forceinline__ void load_x(const uint16_t* __restrict__ x, int B, in
         }
     }
     (void)bn;
+}
+
+// Batched activations (NB = 2 or 4 live columns, even row stride B): consecutive lanes load consecutive rows of
+// x (coalesced), the rows are transposed through a wave-private LDS buffer, and every lane ends up with
+// xr[t][p] = (x[j][t], x[j + 1][t]) for its own 32 rows j = slice_base + 32 lane + 2p.  The slice is staged in
+// one round (whole slice, 64 lane groups) when LDS allows, else four rounds of 512 rows (16 lane groups); the
+// 16-byte pad per lane group keeps the 128-bit reads free of bank conflicts.  Rows past N load row N - 1 (their lanes' activations
+// are zeroed by the caller).
+template <int NB, int XG>
+struct XStage {
+    static constexpr int kGroupBytes = 64 * NB + 16;       // 32 rows * NB halves + pad
+    static constexpr int kBytes = XG * kGroupBytes;        // per wave; XG = lane groups staged per round (16 or 64)
+};
+
+template <int NB, int XG>
+__device__ __forceinline__ void load_x_staged(const uint16_t* __restrict__ x, int B, int N, int slice_base, int lane, char* __restrict__ buf, u32 (&xr)[NB][16]) {
+    constexpr int RW = NB / 2;                              // dwords per row window
+    constexpr int GB = XStage<NB, XG>::kGroupBytes;
+    constexpr int ROUNDS = 64 / XG, LOADS = XG / 2;         // a round stages XG * 32 rows with XG / 2 loads per lane
+#pragma unroll
+    for (int t = 0; t < NB; ++t)
+#pragma unroll
+        for (int p = 0; p < 16; ++p) xr[t][p] = 0;
+#pragma unroll 1
+    for (int r = 0; r < ROUNDS; ++r) {
+        u32 v[LOADS][RW];
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int row = min(slice_base + XG * 32 * r + 64 * i + lane, N - 1);
+            const u32* src = reinterpret_cast<const u32*>(x + (size_t)row * B);
+#pragma unroll
+            for (int h = 0; h < RW; ++h) v[i][h] = src[h];
+        }
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int lr = 64 * i + lane;                    // local row: group lr / 32, row lr % 32
+            u32* dst = reinterpret_cast<u32*>(buf + (lr >> 5) * GB + (lr & 31) * (NB * 2));
+#pragma unroll
+            for (int h = 0; h < RW; ++h) dst[h] = v[i][h];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (lane / XG == r) {
+            const u32* src = reinterpret_cast<const u32*>(buf + (lane % XG) * GB);
+#pragma unroll
+            for (int p = 0; p < 16; ++p) {
+#pragma unroll
+                for (int h = 0; h < RW; ++h) {
+                    const u32 a = src[(2 * p) * RW + h], b = src[(2 * p + 1) * RW + h];   // rows 2p and 2p + 1
+                    xr[2 * h][p] = __builtin_amdgcn_perm(b, a, 0x05040100u);             // (a.lo, b.lo)
+                    xr[2 * h + 1][p] = __builtin_amdgcn_perm(b, a, 0x07060302u);         // (a.hi, b.hi)
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
 }
 
 // table look-ups of one row slice: 16 dwords, each an fp16 pair
@@ -252,9 +298,10 @@ __device__ __forceinline__ void row_block_reduce(float (&v)[C], int lane) {
 // segment adds to the wave's private LDS slot of that row: no floating-point atomics, fixed summation order.
 template <int NB, int UB>
 struct SparseRegs {
+    static constexpr int XW = (NB + 1) / 2;   // dwords holding the NB gathered activations of one nonzero
     int c[UB];
     uint16_t vb[UB];
-    uint16_t xb[UB][NB];
+    u32 xw[UB][XW];
 };
 
 struct SparseRange {
@@ -275,12 +322,20 @@ __device__ __forceinline__ void sparse_issue_cols_vals(const MatvecArgs& g, cons
     }
 }
 
+// x points at the first live batch column; with NB >= 2 the row stride is even and the window starts at a
+// multiple of 4 columns, so the NB activations of a nonzero are whole dwords
 template <int NB, int UB>
 __device__ __forceinline__ void sparse_issue_gathers(const MatvecArgs& g, const uint16_t* __restrict__ x, SparseRegs<NB, UB>& q) {
 #pragma unroll
-    for (int k = 0; k < UB; ++k)
+    for (int k = 0; k < UB; ++k) {
+        if constexpr (NB == 1) {
+            q.xw[k][0] = x[(size_t)q.c[k] * g.B];
+        } else {
+            const u32* src = reinterpret_cast<const u32*>(x + (size_t)q.c[k] * g.B);
 #pragma unroll
-        for (int t = 0; t < NB; ++t) q.xb[k][t] = x[(size_t)q.c[k] * g.B + t];
+            for (int h = 0; h < NB / 2; ++h) q.xw[k][h] = src[h];
+        }
+    }
 }
 
 // LDS float add without a returned value: queued in order behind the wave's earlier LDS operations.  Only one
@@ -302,7 +357,8 @@ __device__ __forceinline__ void sparse_reduce(const SparseRange& sr, const int (
             const bool ok = p <= p_last;
             float v[NB];
 #pragma unroll
-            for (int t = 0; t < NB; ++t) v[t] = ok ? half_bits_to_float(q.vb[k]) * half_bits_to_float(q.xb[k][t]) : 0.f;
+            for (int t = 0; t < NB; ++t)
+                v[t] = ok ? half_bits_to_float(q.vb[k]) * half_bits_to_float((uint16_t)(q.xw[k][t >> 1] >> (16 * (t & 1)))) : 0.f;
             int row_first = 0, row_last = 0;                         // rows of the batch's first / last nonzero
 #pragma unroll
             for (int i = 1; i < R; ++i) { row_first += (p_first >= rp[i]) ? 1 : 0; row_last += (p_last >= rp[i]) ? 1 : 0; }
@@ -371,7 +427,7 @@ __device__ __forceinline__ void sparse_round(const MatvecArgs& g, const uint16_t
 #endif
     sparse_issue_gathers<NB, U>(g, x, q);
 #ifdef SQLLM_TRACE
-    { int acc = 0; for (int k = 0; k < U; ++k) acc += q.xb[k][0]; if (acc == 0x7fffffff) slots[0] = 1.f; }
+    { int acc = 0; for (int k = 0; k < U; ++k) acc += (int)q.xw[k][0]; if (acc == 0x7fffffff) slots[0] = 1.f; }
     SQ_TRACE(3);
 #endif
     sparse_reduce<NB, R, U>(sr, rp, b0, NW, lane, q, slots);
@@ -395,16 +451,17 @@ __device__ __forceinline__ void load_row_pointers(const MatvecArgs& g, int r0, i
     sr.P0 = rp[0]; sr.P1 = rp[R]; sr.nbatch = (sr.P1 - sr.P0 + kWave - 1) / kWave;
 }
 
-template <int BITS, int NB, int R, int D, int MAXT>
+template <int BITS, int NB, int R, int D, int MAXT, int XG>
 __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
     static_assert(D >= 2 && D <= R, "prefetch depth");
     constexpr int E = TableShape<BITS>::kEntries, K = 1 << BITS;
     constexpr int kRawLanes = R * TableShape<BITS>::kRowBytes / 16;  // lanes that fetch 16 bytes of fp16 tables
-    constexpr int UB = NB == 1 ? 8 : (NB == 2 ? 4 : 2);              // sparse batches per wave and round
+    constexpr int UB = 8;                                            // sparse batches per wave and round
     __shared__ u32 tables[R * E];
     __shared__ __align__(16) uint16_t raw[R * K];
     __shared__ float part[kMaxDenseWaves * 4 * R * NB];              // dense:  [wave][16-lane row][r][t]
     __shared__ float spart[(kMaxDenseWaves + 1) * R * NB];           // sparse: [wave][r][t]
+    extern __shared__ __align__(16) char xstage[];                   // batched launches: W * XStage<NB, XG>::kBytes
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int NW = blockDim.x >> 6;
@@ -436,7 +493,8 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
         const bool live = j0 < g.N;
         const int j0c = live ? j0 : g.N - kLaneElems;
         u32 xr[NB][16];
-        load_x<NB>(x, B, bn, j0c, xr);
+        if constexpr (NB == 1) load_x<NB>(x, B, bn, j0c, xr);
+        else load_x_staged<NB, XG>(x, B, g.N, wave * kSliceCols, lane, xstage + wave * XStage<NB, XG>::kBytes, xr);
         const size_t row_dwords = (size_t)g.N * BITS / 32;
         const u32* __restrict__ qlane = static_cast<const u32*>(g.qidx) + (size_t)(j0c / 32) * BITS;
         LaneChunk<BITS> c[R];
@@ -644,12 +702,17 @@ static hipError_t launch_matvec_r(const MatvecArgs& g, hipStream_t s) {
     // batched kernels hold 32 * NB activations per lane: give them the larger register budget of a block
     // of at most 512 threads whenever the row is narrow enough
     if constexpr (NB > 1) {
-        if (waves * kWave <= 512) {
-            hipLaunchKernelGGL((matvec_kernel<BITS, NB, R, D, 512>), dim3(grid), dim3(waves * kWave), 0, s, g);
-            return hipGetLastError();
+        // stage the whole activation slice of a wave at once when the buffers of the block stay within 80 KB (two blocks per compute unit)
+        if ((size_t)W * XStage<NB, 64>::kBytes <= 80 * 1024) {
+            const size_t stage = (size_t)W * XStage<NB, 64>::kBytes;
+            hipLaunchKernelGGL((matvec_kernel<BITS, NB, R, D, 1024, 64>), dim3(grid), dim3(waves * kWave), stage, s, g);
+        } else {
+            const size_t stage = (size_t)W * XStage<NB, 16>::kBytes;
+            hipLaunchKernelGGL((matvec_kernel<BITS, NB, R, D, 1024, 16>), dim3(grid), dim3(waves * kWave), stage, s, g);
         }
+        return hipGetLastError();
     }
-    hipLaunchKernelGGL((matvec_kernel<BITS, NB, R, D, 1024>), dim3(grid), dim3(waves * kWave), 0, s, g);
+    hipLaunchKernelGGL((matvec_kernel<BITS, NB, R, D, 1024, 16>), dim3(grid), dim3(waves * kWave), 0, s, g);
     return hipGetLastError();
 }
 
