@@ -17,9 +17,6 @@ struct MatvecArgs {
     const void* vals;
     const void* x;
     void* y;
-#ifdef SQLLM_TRACE
-    unsigned long long* trace;   // per (block, wave) cycle stamps; stand-alone timing harness only
-#endif
 };
 
 hipError_t launch_matvec(const MatvecArgs& g, hipStream_t s);

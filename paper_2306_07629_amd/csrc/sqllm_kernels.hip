@@ -410,28 +410,13 @@ __device__ __forceinline__ void sparse_reduce(const SparseRange& sr, const int (
     }
 }
 
-#ifdef SQLLM_TRACE
-#define SQ_TRACE(slot) do { if (g.trace && lane == 0) g.trace[((size_t)blockIdx.x * 32 + (threadIdx.x >> 6)) * 8 + (slot)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define SQ_TRACE(slot) do { } while (0)
-#endif
-
 template <int NB, int R, int U>
 __device__ __forceinline__ void sparse_round(const MatvecArgs& g, const uint16_t* __restrict__ x, const SparseRange& sr, const int (&rp)[R + 1],
                                              int b0, int NW, int lane, float* __restrict__ slots) {
     SparseRegs<NB, U> q;
     sparse_issue_cols_vals<NB, U>(g, sr, b0, NW, lane, q);
-#ifdef SQLLM_TRACE
-    { int acc = 0; for (int k = 0; k < U; ++k) acc += q.c[k] + q.vb[k]; if (acc == 0x7fffffff) slots[0] = 1.f; }   // wait for the loads
-    SQ_TRACE(2);
-#endif
     sparse_issue_gathers<NB, U>(g, x, q);
-#ifdef SQLLM_TRACE
-    { int acc = 0; for (int k = 0; k < U; ++k) acc += (int)q.xw[k][0]; if (acc == 0x7fffffff) slots[0] = 1.f; }
-    SQ_TRACE(3);
-#endif
     sparse_reduce<NB, R, U>(sr, rp, b0, NW, lane, q, slots);
-    SQ_TRACE(4);
 }
 
 // ---------------------------------------------------------------------------------------------- the matvec kernel
@@ -480,7 +465,6 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
     int next_batch = 0;                                              // first batch not yet handled (uniform)
 
     if (wave < W) {
-        SQ_TRACE(0);
         // ---- dense wave.  Issue order: (wave 0: fp16 tables), activations, first D rows of the index stream.
         u32x4 rawv = {0, 0, 0, 0};
         if (wave == 0 && lane < kRawLanes) {
@@ -542,10 +526,8 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
         next_batch = UB;                                             // the sparse wave takes batches 0 .. UB-1
     } else {
         // ---- sparse wave(s)
-        SQ_TRACE(0);
         if (dense) {
             __syncthreads();                                          // the dense waves' table barrier
-            SQ_TRACE(1);
             if (sr.nbatch > 2) sparse_round<NB, R, UB>(g, x, sr, rp, 0, 1, lane, myslots);
             else if (sr.nbatch > 0) sparse_round<NB, R, 2>(g, x, sr, rp, 0, 1, lane, myslots);
             next_batch = UB;
@@ -555,7 +537,6 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
     //      (b - next_batch) mod NW, UB batches per wave and round
     for (int b0 = next_batch + wave; b0 < sr.nbatch; b0 += NW * UB)   // uniform
         sparse_round<NB, R, UB>(g, x, sr, rp, b0, NW, lane, myslots);
-    SQ_TRACE(5);
     __syncthreads();
 
     // combine the slice sums and the sparse partial sums in a fixed order, round once
