@@ -27,11 +27,10 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
-def _load():
-    global _lib
-    if _lib is None:
-        build()
-        L = ctypes.CDLL(_LIB)
+def _bind(path):
+    """ctypes signatures of an oracle library (the default build, or a deliberately broken copy in a test)"""
+    if True:
+        L = ctypes.CDLL(path)
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
         L.orc_half_to_double.argtypes = [ctypes.c_uint16]; L.orc_half_to_double.restype = ctypes.c_double
         L.orc_unpack.argtypes = [i32, i32, i32, vp, vp]; L.orc_unpack.restype = None
@@ -40,8 +39,34 @@ def _load():
         L.orc_matvec_rows.restype = None
         L.orc_fp16_matvec.argtypes = [i32, i32, i32, vp, vp, vp, vp]; L.orc_fp16_matvec.restype = None
         L.orc_threads.argtypes = []; L.orc_threads.restype = i32
-        _lib = L
+    return L
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = _bind(_LIB)
     return _lib
+
+
+class use_library:
+    """Context manager: route every call of this module through another build of the oracle source
+    (tests plant mistakes in a copy of the C file and check that the pins notice)."""
+
+    def __init__(self, path):
+        self.path = path
+
+    def __enter__(self):
+        global _lib
+        self.saved = _lib
+        _lib = _bind(self.path)
+        return self
+
+    def __exit__(self, *exc):
+        global _lib
+        _lib = self.saved
+        return False
 
 
 def _p(a):
