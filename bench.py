@@ -28,8 +28,16 @@ WORKLOADS = {
     "llama7b_mlp_pair_3bit": ([(11008, 4096), (4096, 11008)], 3, 0.0045, (0.10, 0.50), 1),
     "llama7b_mlp_pair_4bit": ([(11008, 4096), (4096, 11008)], 4, 0.0045, (0.10, 0.50), 1),
     "single_4096_4bit": ([(4096, 4096)], 4, 0.0045, None, 1),
-    "llama13b_mlp_pair_3bit": ([(13824, 5120), (5120, 13824)], 3, 0.0045, (0.10, 0.50), 1),
+    "llama13b_attn_3bit": ([(5120, 5120)], 3, 0.0045, None, 1),
+    "llama13b_attn_4bit": ([(5120, 5120)], 4, 0.0045, None, 1),
+    "llama13b_mlp_pair_3bit": ([(13824, 5120), (5120, 13824)], 3, 0.0045, None, 1),
+    "llama13b_mlp_pair_4bit": ([(13824, 5120), (5120, 13824)], 4, 0.0045, None, 1),
+    "llama13b_up_3bit_sparse0.05": ([(13824, 5120)], 3, 0.0005, None, 1),
+    "llama13b_up_3bit_sparse1.0": ([(13824, 5120)], 3, 0.01, None, 1),
+    "llama7b_block_3bit": ([(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 3, 0.0045, (0.10, 0.50), 1),
+    "llama65b_attn_3bit": ([(8192, 8192)], 3, 0.0045, (0.01, 0.30), 1),
     "llama65b_mlp_pair_3bit": ([(22016, 8192), (8192, 22016)], 3, 0.0045, (0.01, 0.30), 1),
+    "llama65b_attn_3bit_batch4": ([(8192, 8192)], 3, 0.0045, (0.01, 0.30), 4),
 }
 
 
@@ -204,9 +212,9 @@ def main():
                   else "us per dense+sparse matvec (4-bit LUT + 0.45% CSR), effective HBM GB/s in roofline",
         "value": us_per_matvec, "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec_cold / args.steps * 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 storage, f32 accumulate", "data": "synthetic",
+        "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "layers": [f"{M}x{N}" for M, N in shapes], "bits": bits, "sparse_frac": frac,
-                   "skew": skew, "batch": B, "seed": SEED, "weight_copies_rotated": copies,
+                   "skew": skew, "batch": B, "seed": SEED, "storage": "fp16 tables / CSR values / x / y, fp32 accumulation", "weight_copies_rotated": copies,
                    "working_set_gb": step_bytes * copies / 1e9, "matvecs_per_step": len(shapes)},
         "effective_gbs": gbs, "pct_of_hbm_roofline": 100.0 * gbs / HBM_PEAK_GBS,
         "warm_us_per_matvec": sec_warm / launches * 1e6, "warm_effective_gbs": step_bytes * args.steps / sec_warm / 1e9,
