@@ -706,8 +706,8 @@ static hipError_t launch_matvec_t(const MatvecArgs& g, hipStream_t s) {
         return g.rows_per_wg <= 4 ? launch_matvec_r<BITS, NB, 4, 2>(g, s) : launch_matvec_r<BITS, NB, 8, 2>(g, s);
     } else {
         if (g.rows_per_wg <= 2) return launch_matvec_r<BITS, NB, 2, 2>(g, s);
-        if (g.rows_per_wg <= 4) return launch_matvec_r<BITS, NB, 4, 4>(g, s);
-        if (g.rows_per_wg <= 8) return launch_matvec_r<BITS, NB, 8, 4>(g, s);
+        if (g.rows_per_wg <= 4) return launch_matvec_r<BITS, NB, 4, 2>(g, s);
+        if (g.rows_per_wg <= 8) return launch_matvec_r<BITS, NB, 8, 2>(g, s);
         return launch_matvec_r<BITS, NB, 16, 4>(g, s);
     }
 }
