@@ -35,6 +35,9 @@ WORKLOADS = {
     "llama13b_up_3bit_sparse0.05": ([(13824, 5120)], 3, 0.0005, None, 1),
     "llama13b_up_3bit_sparse1.0": ([(13824, 5120)], 3, 0.01, None, 1),
     "llama7b_block_3bit": ([(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 3, 0.0045, (0.10, 0.50), 1),
+    # the same block with the projections that share an input stacked row-wise (q,k,v -> 12288 rows; gate,up ->
+    # 22016 rows): exact, because every output row has its own table; 4 launches per block instead of 7
+    "llama7b_block_3bit_stacked": ([(12288, 4096), (4096, 4096), (22016, 4096), (4096, 11008)], 3, 0.0045, (0.10, 0.50), 1),
     "llama65b_attn_3bit": ([(8192, 8192)], 3, 0.0045, (0.01, 0.30), 1),
     "llama65b_mlp_pair_3bit": ([(22016, 8192), (8192, 22016)], 3, 0.0045, (0.01, 0.30), 1),
     "llama65b_attn_3bit_batch4": ([(8192, 8192)], 3, 0.0045, (0.01, 0.30), 4),
@@ -216,7 +219,7 @@ def main():
         "config": {"workload": args.workload, "layers": [f"{M}x{N}" for M, N in shapes], "bits": bits, "sparse_frac": frac,
                    "skew": skew, "batch": B, "seed": SEED, "storage": "fp16 tables / CSR values / x / y, fp32 accumulation", "weight_copies_rotated": copies,
                    "working_set_gb": step_bytes * copies / 1e9, "matvecs_per_step": len(shapes)},
-        "effective_gbs": gbs, "pct_of_hbm_roofline": 100.0 * gbs / HBM_PEAK_GBS,
+        "effective_gbs": gbs, "pct_of_hbm_roofline": 100.0 * gbs / HBM_PEAK_GBS, "us_per_step": sec_cold / args.steps * 1e6,
         "warm_us_per_matvec": sec_warm / launches * 1e6, "warm_effective_gbs": step_bytes * args.steps / sec_warm / 1e9,
         "fp16_gemv_us": {"own_kernel": us_f_own, "torch_mv": us_f_torch}, "speedup_vs_fp16": us_f / us_per_matvec,
         "parity_worst_err_over_bound": worst, "launch_mode": "hip_graph_replay" if G else "python_ctypes", "host_wall_s_timed_region": wall_cold,
