@@ -4,18 +4,18 @@
 // one fp16 table per output row, S in CSR with fp16 values.  The storage format is described in sqllm.h.
 //
 // Work decomposition of the matvec kernel
-//   * A workgroup owns R consecutive rows (R = 4, 8 or 16, compile time) and all N columns.
+//   * A workgroup owns R consecutive rows (R = 2, 4, 8 or 16, compile time) and all N columns.
 //   * Dense waves: wave w owns the 2048-column slice [2048 w, 2048 w + 2048): lane l keeps the 32 activations
 //     x[2048 w + 32 l .. +32) in registers for the whole kernel (x is read once per workgroup) and, per row,
 //     loads its 32 indices (12 bytes for b = 3, 16 bytes for b = 4; the wave reads 768 / 1024 contiguous
-//     bytes of the row).  All R row loads are issued before the first is consumed.
+//     bytes of the row).  D rows are requested up front, row u + D when row u has been handed to the look-ups.
 //   * Dequantisation goes through PAIR TABLES in LDS: for every row of the block the workgroup first builds
 //       b = 3:  64 entries,  entry (a | c << 3) = (lut[a], lut[c]) as two fp16 in one dword   (256 B / row)
 //       b = 4: 256 entries,  entry (a | c << 4) = (lut[a], lut[c])                            (1 KB / row)
 //     so ONE ds_read_b32, addressed by a 6- or 8-bit field of the index stream (two neighbouring indices),
 //     returns a ready-made fp16 pair for v_dot2_f32_f16 (two products, fp32 accumulate).  Measured on MI355X
-//     this costs ~2.1 (64 entries) / ~5.5 (256 entries) LDS cycles per wave-wide look-up of 128 weights,
-//     against ~7.3 for a ds_bpermute-based register table.  The field extraction is a shift + mask
+//     a wave-wide look-up occupies the LDS for ~4 cycles (64 entries) / ~7 cycles (256 entries, bank
+//     conflicts), against ~7.3 for a ds_bpermute-based register table.  The field extraction is a shift + mask
 //     (a funnel shift where a 3-bit pair straddles two dwords; a byte select for b = 4).
 //   * Per row the 64 lane sums are reduced with DPP adds (no LDS traffic), the slice sums of the W waves
 //     are combined through LDS in a fixed order, the CSR term is added, and y is rounded to fp16 once.
