@@ -38,6 +38,7 @@ def _load():
         vp, i32, i64, u64, f64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64, ctypes.c_double
         L.sqgen_weights.argtypes = [i32, i32, u64, vp]; L.sqgen_weights.restype = None
         L.sqgen_x.argtypes = [i32, i32, u64, vp]; L.sqgen_x.restype = None
+        L.sqgen_sens.argtypes = [i32, i32, u64, vp]; L.sqgen_sens.restype = None
         L.sqgen_nnz.argtypes = [i32, i32, f64]; L.sqgen_nnz.restype = i64
         L.sqgen_counts_skewed.argtypes = [i32, i32, i64, f64, f64, u64, vp]; L.sqgen_counts_skewed.restype = i32
         L.sqgen_select_global.argtypes = [i32, i32, i64, vp, vp, vp]; L.sqgen_select_global.restype = i32
@@ -101,6 +102,13 @@ def make_weights(M: int, N: int, seed: int) -> np.ndarray:
     w = np.empty((M, N), dtype=np.uint16)
     _load().sqgen_weights(M, N, seed, _p(w))
     return w
+
+
+def make_sens(M: int, N: int, seed: int) -> np.ndarray:
+    """Synthetic per-weight sensitivities, uint16 [M, N] (stand-in for the diagonal Fisher information)."""
+    s = np.empty((M, N), dtype=np.uint16)
+    _load().sqgen_sens(M, N, seed, _p(s))
+    return s
 
 
 def pack(idx: np.ndarray, bits: int) -> np.ndarray:

@@ -124,6 +124,24 @@ void sqgen_x(int N, int B, uint64_t seed, uint16_t *x16) {
     }
 }
 
+/* Synthetic per-weight sensitivities (stand-in for the diagonal Fisher information of Sec. 4.1, which needs a
+ * model and calibration data): squared-gradient-like values g^2 with g = z1 * exp(0.75 z2), heavy-tailed so that
+ * a few weights of every row dominate, scaled by 64 and stored as 16-bit unsigned integers (saturating). */
+void sqgen_sens(int M, int N, uint64_t seed, uint16_t *s16) {
+    const int64_t total = (int64_t)M * N;
+    #pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < total; ++e) {
+        double u1 = rng_u01(seed, 7, 4 * (uint64_t)e + 0);
+        double u2 = rng_u01(seed, 7, 4 * (uint64_t)e + 1);
+        double u3 = rng_u01(seed, 7, 4 * (uint64_t)e + 2);
+        double u4 = rng_u01(seed, 7, 4 * (uint64_t)e + 3);
+        double z1 = sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925 * u2);
+        double z2 = sqrt(-2.0 * log(u3)) * cos(6.283185307179586476925 * u4);
+        double v = floor(64.0 * z1 * z1 * exp(1.5 * z2));
+        s16[e] = (uint16_t)(v > 65535.0 ? 65535.0 : v);
+    }
+}
+
 /* number of sparse entries for a sparsity level */
 int64_t sqgen_nnz(int M, int N, double frac) { return llround(frac * (double)M * (double)N); }
 
