@@ -100,6 +100,36 @@ int sqllm_dequantize(int M, int N, int bits, const void* qidx, const void* lut, 
  * W fp16 [M][N] row-major, fp32 accumulation, fp16 result.  N % 8 == 0, w and x 16-byte aligned.         */
 int sqllm_fp16_gemv(int M, int N, int B, const void* w, const void* x, void* y, void* stream);
 
+/* ---- Offline side: Dense-and-Sparse split and sensitivity-weighted k-means (Sec. 4.1, Eq. 4; Sec. 4.2) ----
+ * One call turns an fp16 weight matrix into everything the matvec reads.  All pointers are device pointers.
+ *   w      fp16   [M][N] row-major, finite values                      (in)
+ *   sens   uint16 [M][N] per-weight sensitivity: the diagonal Fisher information of Eq. 4 scaled to 16 bits by the
+ *                        caller; only ratios inside a row matter for the tables, the order across the matrix for
+ *                        the extraction                                  (in)
+ *   n_lo, n_hi, n_sens   Sec. 4.2 thresholds as counts: T_min is the n_lo-th smallest weight of the matrix, T_max the
+ *                        n_hi-th largest, and the sensitivity threshold the n_sens-th largest sensitivity (0-based).
+ *                        A weight is extracted iff w < T_min or w > T_max or its sensitivity is above the threshold
+ *                        (strict comparisons: ties stay dense, so at most n_lo + n_hi + n_sens entries are extracted;
+ *                        -0 counts as smaller than +0).  All three 0 -> nothing is extracted.
+ *   max_iter             upper bound on the centroid updates per row; iteration stops earlier when no weight changes
+ *                        its cluster.
+ *   workspace            sqllm_quantize_workspace_bytes(M, N) bytes of scratch, 4-byte aligned; contents are
+ *                        overwritten; calls sharing a workspace must not overlap.
+ *   qidx, lut            out: packed indices and fp16 tables (ascending per row) in the layout described above.
+ *                        Per row the tables minimise sum_j sens_j (w_j - lut[idx_j])^2 over the dense weights by
+ *                        Lloyd iterations from an equal-count start; idx_j is the nearest table entry (ties to the
+ *                        lower index).  An extracted position gets the index of the entry nearest to zero.
+ *   rowptr, cols, vals   out: CSR of the extracted weights (their full fp16 values, columns ascending);
+ *                        rowptr int32 [M + 1]; cols / vals need room for n_lo + n_hi + n_sens entries;
+ *                        the number written is rowptr[M].
+ *   iters                out, may be NULL: int32 [M], centroid updates performed per row.
+ * The results are a pure function of the inputs (integer accumulation, fixed-precision decisions): run-to-run
+ * identical.  Errors as for the other entry points; M * N must be below 2^32.                                   */
+long long sqllm_quantize_workspace_bytes(int M, int N);
+int sqllm_quantize_layer(int M, int N, int bits, int max_iter, const void* w, const void* sens,
+                         long long n_lo, long long n_hi, long long n_sens, void* workspace, long long workspace_bytes,
+                         void* qidx, void* lut, int* rowptr, int* cols, void* vals, int* iters, void* stream);
+
 /* Bytes the method moves for one matvec (indices + tables + CSR arrays + x + y); used for GB/s figures.  */
 long long sqllm_algorithmic_bytes(int M, int N, int bits, long long nnz, int B);
 

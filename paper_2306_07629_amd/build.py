@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsqllm.so")
-SOURCES = ["sqllm_kernels.hip", "sqllm_api.cpp"]
+SOURCES = ["sqllm_kernels.hip", "sqllm_quant.hip", "sqllm_api.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed-FP32 instructions are kept out of the generated code on purpose

@@ -173,6 +173,38 @@ long long sqllm_algorithmic_bytes(int M, int N, int bits, long long nnz, int B) 
     return b;
 }
 
+long long sqllm_quantize_workspace_bytes(int M, int N) {
+    (void)M; (void)N;
+    return (long long)sqllm::quantize_workspace_bytes();
+}
+
+int sqllm_quantize_layer(int M, int N, int bits, int max_iter, const void* w, const void* sens,
+                         long long n_lo, long long n_hi, long long n_sens, void* workspace, long long workspace_bytes,
+                         void* qidx, void* lut, int* rowptr, int* cols, void* vals, int* iters, void* stream) {
+    int st;
+    if ((st = check_bits(bits)) || (st = check_shape(M, N, 1))) return st;
+    if (M == 0) return SQLLM_OK;
+    const long long total = (long long)M * N;
+    if (total >= (1ll << 32)) return fail(SQLLM_ERR_SHAPE, "M * N = %lld does not fit the 32-bit histogram counters", total);
+    if (max_iter < 0) return fail(SQLLM_ERR_SHAPE, "max_iter = %d is negative", max_iter);
+    if (n_lo < 0 || n_hi < 0 || n_sens < 0 || n_lo >= total || n_hi >= total || n_sens >= total || n_lo + n_hi + n_sens >= (1ll << 31))
+        return fail(SQLLM_ERR_NNZ, "extraction counts (%lld, %lld, %lld) out of range for %lld weights", n_lo, n_hi, n_sens, total);
+    if (!w || !sens || !workspace || !qidx || !lut || !rowptr) return fail(SQLLM_ERR_NULL, "a required pointer is NULL");
+    if (n_lo + n_hi + n_sens > 0 && (!cols || !vals)) return fail(SQLLM_ERR_NULL, "cols / vals are NULL although entries may be extracted");
+    if (workspace_bytes < (long long)sqllm::quantize_workspace_bytes())
+        return fail(SQLLM_ERR_SHAPE, "workspace of %lld bytes, %lld needed", workspace_bytes, (long long)sqllm::quantize_workspace_bytes());
+    if (((uintptr_t)w | (uintptr_t)sens | (uintptr_t)qidx | (uintptr_t)lut) & 15) return fail(SQLLM_ERR_ALIGN, "w, sens, qidx and lut must be 16-byte aligned");
+    if (((uintptr_t)workspace | (uintptr_t)rowptr | (uintptr_t)cols | (uintptr_t)iters) & 3) return fail(SQLLM_ERR_ALIGN, "workspace, rowptr, cols and iters must be 4-byte aligned");
+    if ((uintptr_t)vals & 1) return fail(SQLLM_ERR_ALIGN, "vals must be 2-byte aligned");
+    sqllm::QuantArgs a;
+    memset(&a, 0, sizeof a);
+    a.M = M; a.N = N; a.bits = bits; a.max_iter = max_iter; a.n_lo = n_lo; a.n_hi = n_hi; a.n_sens = n_sens;
+    a.w = w; a.sens = sens; a.workspace = workspace; a.qidx = qidx; a.lut = lut; a.rowptr = rowptr; a.cols = cols; a.vals = vals; a.iters = iters;
+    const hipError_t e = sqllm::launch_quantize(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "quantize launch");
+    return SQLLM_OK;
+}
+
 int sqllm_set_rows_per_workgroup(int rows) {
     const int old = g_rows_per_wg;
     g_rows_per_wg = rows < 0 ? 0 : (rows > 64 ? 64 : rows);

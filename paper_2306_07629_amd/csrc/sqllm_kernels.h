@@ -19,6 +19,23 @@ struct MatvecArgs {
     void* y;
 };
 
+// Offline side (sqllm_quant.hip): everything is a caller-owned device pointer.
+struct QuantArgs {
+    int M, N, bits, max_iter;
+    long long n_lo, n_hi, n_sens;
+    const void* w;          // fp16 [M][N]
+    const void* sens;       // uint16 [M][N]
+    void* workspace;        // quantize_workspace_bytes() bytes
+    void* qidx;             // out: packed indices
+    void* lut;              // out: fp16 [M][2^bits]
+    int* rowptr;            // out: [M + 1]
+    int* cols;              // out: capacity n_lo + n_hi + n_sens
+    void* vals;             // out: fp16, same capacity
+    int* iters;             // out, optional: [M]
+};
+size_t quantize_workspace_bytes();
+hipError_t launch_quantize(const QuantArgs& a, hipStream_t s);
+
 hipError_t launch_matvec(const MatvecArgs& g, hipStream_t s);
 hipError_t launch_csr_rowwise(const MatvecArgs& g, hipStream_t s);
 hipError_t launch_decode(int M, int N, int bits, const void* qidx, const void* lut, void* idx_out, void* w_out, hipStream_t s);
