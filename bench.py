@@ -44,12 +44,93 @@ WORKLOADS = {
 }
 
 
+# offline side: one step = one whole sqllm_quantize_layer call (split + weighted k-means) on one matrix
+QUANT_WORKLOADS = {
+    # name: (M, N, bits, outlier share, sensitive share, max centroid updates)
+    "quantize_llama7b_attn_3bit": (4096, 4096, 3, 0.004, 0.0005, 32),
+    "quantize_llama7b_up_3bit": (11008, 4096, 3, 0.004, 0.0005, 32),
+    "quantize_llama7b_down_4bit": (4096, 11008, 4, 0.004, 0.0005, 32),
+}
+ALU_PEAK_TOPS = 39.3   # 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz: one integer / compare lane operation per lane and clock
+
+
+def bench_quantize(args):
+    import numpy as np
+    import torch
+    import gen
+    import paper_2306_07629_amd as sq
+    from oracle import quant_oracle as qo   # parity gate and cpu_baseline leg only
+
+    M, N, bits, of, sf, max_iter = QUANT_WORKLOADS[args.workload]
+    K = 1 << bits
+    w = gen.make_weights(M, N, gen.layer_seed(SEED, 6, 0))
+    s = gen.make_sens(M, N, gen.layer_seed(SEED, 6, 0))
+    n_lo, n_hi, n_sens = sq.extraction_counts(M, N, of, sf)
+    wd = torch.from_numpy(w.view(np.int16)).cuda()
+    sd = torch.from_numpy(s.view(np.int16)).cuda()
+    q = sq.quantize_layer(wd, sd, bits, n_lo, n_hi, n_sens, max_iter)
+    torch.cuda.synchronize()
+
+    # ---- parity gate: the split in full, tables / indices / iteration counts on a sample of rows
+    rows = np.unique(np.random.default_rng(1).integers(0, M, 24))
+    t0 = time.perf_counter()
+    thr = qo.thresholds(w, s, n_lo, n_hi, n_sens)
+    mask = qo.split_mask(w, s, thr)
+    rowptr, cols, vals = qo.csr_from_mask(w, mask)
+    t_split = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    ref = qo.quantize_layer(w, s, bits, n_lo, n_hi, n_sens, max_iter, rows=rows)
+    t_rows = time.perf_counter() - t0 - t_split           # quantize_layer repeats the split
+    import oracle
+    nnz = q.nnz()
+    idx = oracle.unpack(M, N, bits, q.qidx.cpu().numpy())
+    ok = (np.array_equal(q.rowptr.cpu().numpy(), rowptr) and np.array_equal(q.cols.cpu().numpy()[:nnz], cols)
+          and np.array_equal(q.vals.cpu().numpy().view(np.uint16)[:nnz], vals)
+          and np.array_equal(q.lut.cpu().numpy().view(np.uint16)[rows], ref["lut"][rows]) and np.array_equal(idx[rows], ref["idx"][rows])
+          and np.array_equal(q.iters.cpu().numpy()[rows], ref["iters"][rows]))
+    if not ok:
+        print("bench.py: parity FAILED for the quantised layer", file=sys.stderr)
+        sys.exit(4)
+
+    def step(_):
+        sq.quantize_layer(wd, sd, bits, n_lo, n_hi, n_sens, max_iter)
+
+    sec, wall = time_steps(torch, step, args.steps, args.warmup, use_graph=False)
+    ms = sec / args.steps * 1e3
+    iters = q.iters.float()
+    mean_it = float(iters.mean().item())
+    # lane operations the method itself needs: per weight and assignment pass K - 1 compare-and-count pairs plus the
+    # exact product and three accumulations; 16 search steps of K compares for the equal-count start; one final pass
+    passes = mean_it + 1
+    ops = M * N * (passes * (2 * (K - 1) + 10) + 16 * 2 * K + 2 * (K - 1) + 10)
+    tops = ops / (sec / args.steps) / 1e12
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = {"value": (t_split + max(t_rows, 0.0) * M / len(rows)) * 1e3, "unit": "ms per layer", "cores": 1, "kind": "oracle",
+               "sample": f"split of the whole matrix ({t_split:.2f} s) + Lloyd iterations on {len(rows)} of {M} rows ({t_rows:.2f} s), scaled to all rows; numpy, one thread"}
+    out = {
+        "metric": "ms per weight matrix quantised (Dense-and-Sparse split + sensitivity-weighted k-means)", "value": ms, "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "i64", "data": "synthetic",
+        "config": {"workload": args.workload, "shape": f"{M}x{N}", "bits": bits, "outlier_share": of, "sensitive_share": sf,
+                   "n_lo": n_lo, "n_hi": n_hi, "n_sens": n_sens, "max_updates": max_iter, "seed": SEED},
+        "mean_updates_per_row": mean_it, "max_updates_seen": int(iters.max().item()), "extracted": nnz,
+        "weights_per_second": M * N / (sec / args.steps), "parity": "bit-exact on the split and on sampled rows",
+        "host_wall_s_timed_region": wall,
+        "roofline": {"bound": "alu", "achieved": tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": tops / ALU_PEAK_TOPS, "traffic": None,
+                     "kernel": f"sqllm::quant_kmeans_kernel<{bits}> (95 % of the call; the 7 split kernels are timed with it)",
+                     "algorithmic_lane_ops_per_launch": ops},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", default="llama7b_mlp_pair_3bit", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="llama7b_mlp_pair_3bit", choices=sorted(WORKLOADS) + sorted(QUANT_WORKLOADS))
     ap.add_argument("--footprint-gb", type=float, default=1.1, help="bytes of distinct weight copies to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rows-per-wg", type=int, default=0)
@@ -110,6 +191,10 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+    if args.workload in QUANT_WORKLOADS:
+        if args.steps == 400 and args.warmup == 40:     # the defaults are sized for the microsecond matvecs
+            args.steps, args.warmup = 20, 3
+        return bench_quantize(args)
     shapes, bits, frac, skew, B = WORKLOADS[args.workload]
     if args.rows_per_wg:
         sq.sqllm_set_rows_per_workgroup(args.rows_per_wg)
