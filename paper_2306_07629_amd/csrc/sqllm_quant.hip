@@ -46,8 +46,12 @@ __global__ void __launch_bounds__(256) quant_clear_kernel(u32* ws) {
 
 // pass 1: histograms of the high bytes of all weight keys and of all sensitivities
 __global__ void __launch_bounds__(256) quant_hist1_kernel(long long units, const u32x4* __restrict__ w, const u32x4* __restrict__ s, u32* __restrict__ ws) {
-    __shared__ u32 hw[256], hs[256];
-    hw[threadIdx.x] = 0; hs[threadIdx.x] = 0;
+    // eight copies of each histogram, picked by the lane, so that the lanes of a wave seldom add to one address
+    __shared__ u32 hw8[8][256], hs8[8][256];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) { hw8[c][threadIdx.x] = 0; hs8[c][threadIdx.x] = 0; }
+    u32* hw = hw8[threadIdx.x & 7];
+    u32* hs = hs8[threadIdx.x & 7];
     __syncthreads();
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < units; i += (long long)gridDim.x * blockDim.x) {
         const u32x4 wv = w[i], sv = s[i];
@@ -59,11 +63,14 @@ __global__ void __launch_bounds__(256) quant_hist1_kernel(long long units, const
         }
     }
     __syncthreads();
-    if (hw[threadIdx.x]) atomicAdd(&ws[kWsHist1W + threadIdx.x], hw[threadIdx.x]);
-    if (hs[threadIdx.x]) atomicAdd(&ws[kWsHist1S + threadIdx.x], hs[threadIdx.x]);
+    u32 tw = 0, ts = 0;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) { tw += hw8[c][threadIdx.x]; ts += hs8[c][threadIdx.x]; }
+    if (tw) atomicAdd(&ws[kWsHist1W + threadIdx.x], tw);
+    if (ts) atomicAdd(&ws[kWsHist1S + threadIdx.x], ts);
 }
 
-// bin holding the element of rank r (0-based) in a 256-bin histogram, and the rank inside that bin
+// bin holding the element of rank r (0-based) in a 256-bin histogram (in LDS), and the rank inside that bin
 __device__ inline void select_bin(const u32* hist, u64 r, u32& bin, u64& residual) {
     u64 cum = 0;
     bin = 255; residual = 0;
@@ -74,14 +81,16 @@ __device__ inline void select_bin(const u32* hist, u64 r, u32& bin, u64& residua
     }
 }
 
-__global__ void quant_select1_kernel(u64 total, u64 n_lo, u64 n_hi, u64 n_sens, u32* ws) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    const u64 ranks[3] = {n_lo, total - 1 - n_hi, total - 1 - n_sens};
-    for (int t = 0; t < 3; ++t) {
-        u32 bin; u64 res;
-        select_bin(ws + (t < 2 ? kWsHist1W : kWsHist1S), ranks[t], bin, res);
-        ws[kWsSel + 4 * t] = bin; ws[kWsSel + 4 * t + 1] = (u32)res; ws[kWsSel + 4 * t + 2] = (u32)(res >> 32);
-    }
+__global__ void __launch_bounds__(256) quant_select1_kernel(u64 total, u64 n_lo, u64 n_hi, u64 n_sens, u32* ws) {
+    __shared__ u32 h[2][256];
+    h[0][threadIdx.x] = ws[kWsHist1W + threadIdx.x]; h[1][threadIdx.x] = ws[kWsHist1S + threadIdx.x];
+    __syncthreads();
+    if (threadIdx.x >= 3) return;
+    const int t = threadIdx.x;
+    const u64 rank = t == 0 ? n_lo : (t == 1 ? total - 1 - n_hi : total - 1 - n_sens);
+    u32 bin; u64 res;
+    select_bin(h[t < 2 ? 0 : 1], rank, bin, res);
+    ws[kWsSel + 4 * t] = bin; ws[kWsSel + 4 * t + 1] = (u32)res; ws[kWsSel + 4 * t + 2] = (u32)(res >> 32);
 }
 
 // pass 2: histograms of the low bytes inside the three selected bins
@@ -110,14 +119,17 @@ __global__ void __launch_bounds__(256) quant_hist2_kernel(long long units, const
         if (h[t][threadIdx.x]) atomicAdd(&ws[kWsHist2 + 256 * t + threadIdx.x], h[t][threadIdx.x]);
 }
 
-__global__ void quant_select2_kernel(u32* ws) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    for (int t = 0; t < 3; ++t) {
-        const u64 r = (u64)ws[kWsSel + 4 * t + 1] | ((u64)ws[kWsSel + 4 * t + 2] << 32);
-        u32 lo; u64 res;
-        select_bin(ws + kWsHist2 + 256 * t, r, lo, res);
-        ws[kWsThr + t] = (ws[kWsSel + 4 * t] << 8) | lo;
-    }
+__global__ void __launch_bounds__(256) quant_select2_kernel(u32* ws) {
+    __shared__ u32 h[3][256];
+#pragma unroll
+    for (int t = 0; t < 3; ++t) h[t][threadIdx.x] = ws[kWsHist2 + 256 * t + threadIdx.x];
+    __syncthreads();
+    if (threadIdx.x >= 3) return;
+    const int t = threadIdx.x;
+    const u64 r = (u64)ws[kWsSel + 4 * t + 1] | ((u64)ws[kWsSel + 4 * t + 2] << 32);
+    u32 lo; u64 res;
+    select_bin(h[t], r, lo, res);
+    ws[kWsThr + t] = (ws[kWsSel + 4 * t] << 8) | lo;
 }
 
 __device__ __forceinline__ bool is_extracted(u32 wbits, u32 sv, u32 key_min, u32 key_max, u32 s_thr) {
@@ -164,50 +176,70 @@ __global__ void __launch_bounds__(1024) quant_scan_kernel(int M, int* __restrict
     for (int i = b; i < e; ++i) { run += rowptr[i + 1]; rowptr[i + 1] = run; }
 }
 
-// sum over the 64 lanes, valid in every lane
+// sums over the 64 lanes, valid in every lane
 __device__ __forceinline__ int wave_sum_all(int v) {
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
     return v;
 }
+__device__ __forceinline__ u64 wave_sum_all(u64 v) {
+    for (int off = 32; off > 0; off >>= 1) v += (u64)__shfl_xor((long long)v, off, 64);
+    return v;
+}
 
-// One block of 256 threads per row.  LDS: the row's weights and sensitivities (bit patterns), one byte of index per
-// weight (0xFF marks an extracted position while the iterations run), and the per-cluster sums.
+// One block of 256 threads per row.  In one dimension the clusters of Lloyd's method are intervals of the sorted
+// weights, so the row is sorted once and every iteration only moves K - 1 boundaries:
+//   * LDS holds the row's dense weights as (key << 16 | sensitivity), sorted ascending by a bitonic network
+//     (extracted positions and the padding up to a power of two are 0xFFFFFFFF and end up behind the dense ones),
+//     and the running sums (sum s, low and high words of sum s w 2^24) in front of every chunk of 64 sorted weights.
+//   * A boundary position p_k = #{ j : fp32(2 w_j) <= fp32(c_k + c_{k+1}) } is found by a 64-way search (every lane
+//     probes one position per round, three rounds cover 2^18 weights); the sums in front of p_k are the chunk's running
+//     sums plus a wave reduction over the part of the chunk before p_k; cluster sums are differences of neighbours.
+//     These are the same decisions and the same exact integer sums as a pass over all weights, hence the same result.
+//   * "No weight changed its cluster" is "no boundary position moved".
+// The final indices and the packed stream are produced from the row as it lies in memory.
 template <int BITS>
-__global__ void __launch_bounds__(256) quant_kmeans_kernel(int M, int N, int max_iter, const uint16_t* __restrict__ w, const uint16_t* __restrict__ sens,
+__global__ void __launch_bounds__(256) quant_kmeans_kernel(int M, int N, int NP, int max_iter, const uint16_t* __restrict__ w, const uint16_t* __restrict__ sens,
                                                          const u32* __restrict__ ws, const int* __restrict__ rowptr, void* __restrict__ qidx,
                                                          uint16_t* __restrict__ lut, int* __restrict__ cols, uint16_t* __restrict__ vals, int* __restrict__ iters) {
     constexpr int K = 1 << BITS, T = 256;
     extern __shared__ __align__(16) char smem[];
-    uint16_t* wl = reinterpret_cast<uint16_t*>(smem);                // [N]
-    uint16_t* sl = wl + N;                                          // [N]
-    uint8_t* il = reinterpret_cast<uint8_t*>(sl + N);               // [N]
-    __shared__ u64 S0[K], S1lo[K], S1hi[K];
+    u32* A = reinterpret_cast<u32*>(smem);                           // [NP]
+    const int NC = NP / 64;
+    u64* c0 = reinterpret_cast<u64*>(A + NP);                        // [NC + 1] running sum of s in front of chunk c
+    u64* clo = c0 + (NC + 1);                                        // low words of s * w * 2^24
+    u64* chi = clo + (NC + 1);                                       // high words (two's complement)
+    __shared__ u64 F0[K + 1], Flo[K + 1], Fhi[K + 1];
     __shared__ float cen[K], thr2[K];
     __shared__ i64 cfix[K];
-    __shared__ int counts[K], scan[T], flags[2];
-    __shared__ u32 prefix[K];
+    __shared__ int scan[T], pos[K + 1], prevpos[K + 1], flag;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, row = blockIdx.x;
     const u32 key_min = ws[kWsThr], key_max = ws[kWsThr + 1], s_thr = ws[kWsThr + 2];
+    const uint16_t* __restrict__ wrow = w + (size_t)row * N;
+    const uint16_t* __restrict__ srow = sens + (size_t)row * N;
 
-    // ---- 1. the row into LDS; mark extracted positions
+    // ---- 1. the row into LDS as sortable words; extracted positions and padding become 0xFFFFFFFF
     {
-        const u32x4* wr = reinterpret_cast<const u32x4*>(w + (size_t)row * N);
-        const u32x4* sr = reinterpret_cast<const u32x4*>(sens + (size_t)row * N);
-        for (int i = tid; i < N / 8; i += T) {
-            const u32x4 wv = wr[i], sv = sr[i];
-            reinterpret_cast<u32x4*>(wl)[i] = wv; reinterpret_cast<u32x4*>(sl)[i] = sv;
-            const u32 wd[4] = {wv.x, wv.y, wv.z, wv.w}, sd[4] = {sv.x, sv.y, sv.z, sv.w};
-            u32 m[2] = {0, 0};
+        const u32x4* wr = reinterpret_cast<const u32x4*>(wrow);
+        const u32x4* sr = reinterpret_cast<const u32x4*>(srow);
+        for (int i = tid; i < NP / 8; i += T) {
+            u32 out[8];
+            if (i < N / 8) {
+                const u32x4 wv = wr[i], sv = sr[i];
+                const u32 wd[4] = {wv.x, wv.y, wv.z, wv.w}, sd[4] = {sv.x, sv.y, sv.z, sv.w};
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const u32 a = is_extracted(wd[k] & 0xFFFFu, sd[k] & 0xFFFFu, key_min, key_max, s_thr) ? 0xFFu : 0xFEu;
-                const u32 b = is_extracted(wd[k] >> 16, sd[k] >> 16, key_min, key_max, s_thr) ? 0xFFu : 0xFEu;
-                m[k >> 1] |= (a | (b << 8)) << (16 * (k & 1));
+                for (int k = 0; k < 4; ++k) {
+                    const u32 w0 = wd[k] & 0xFFFFu, w1 = wd[k] >> 16, s0 = sd[k] & 0xFFFFu, s1 = sd[k] >> 16;
+                    out[2 * k] = is_extracted(w0, s0, key_min, key_max, s_thr) ? 0xFFFFFFFFu : (half_key(w0) << 16) | s0;
+                    out[2 * k + 1] = is_extracted(w1, s1, key_min, key_max, s_thr) ? 0xFFFFFFFFu : (half_key(w1) << 16) | s1;
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) out[k] = 0xFFFFFFFFu;
             }
-            reinterpret_cast<u32*>(il)[2 * i] = m[0]; reinterpret_cast<u32*>(il)[2 * i + 1] = m[1];
+            reinterpret_cast<u32x4*>(A)[2 * i] = u32x4{out[0], out[1], out[2], out[3]};
+            reinterpret_cast<u32x4*>(A)[2 * i + 1] = u32x4{out[4], out[5], out[6], out[7]};
         }
-        if (tid < K) { S0[tid] = 0; S1lo[tid] = 0; S1hi[tid] = 0; counts[tid] = 0; }
     }
     __syncthreads();
 
@@ -215,7 +247,7 @@ __global__ void __launch_bounds__(256) quant_kmeans_kernel(int M, int N, int max
     const int C = (N + T - 1) / T;
     const int jb = min(tid * C, N), je = min(jb + C, N);
     int mine = 0;
-    for (int j = jb; j < je; ++j) mine += il[j] == 0xFF;
+    for (int j = jb; j < je; ++j) mine += A[j] == 0xFFFFFFFFu;
     scan[tid] = mine;
     __syncthreads();
     for (int off = 1; off < T; off <<= 1) {
@@ -228,88 +260,108 @@ __global__ void __launch_bounds__(256) quant_kmeans_kernel(int M, int N, int max
     {
         int o = rowptr[row] + scan[tid] - mine;
         for (int j = jb; j < je; ++j)
-            if (il[j] == 0xFF) { cols[o] = j; vals[o] = wl[j]; ++o; }
+            if (A[j] == 0xFFFFFFFFu) { cols[o] = j; vals[o] = wrow[j]; ++o; }
+    }
+    __syncthreads();
+
+    // ---- 3. bitonic sort, ascending
+    for (int k = 2; k <= NP; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = tid; i < NP / 2; i += T) {
+                const int a = 2 * i - (i & (j - 1)), b = a + j;
+                const u32 va = A[a], vb = A[b];
+                const bool asc = (a & k) == 0;
+                if ((va > vb) == asc) { A[a] = vb; A[b] = va; }
+            }
+            __syncthreads();
+        }
     }
 
-    // ---- 3. equal-count start: centroid k = the dense weight of rank floor((2k + 1) n / (2K)); K bitwise searches over
-    //         the 16-bit keys run together (largest v with #{keys < v} <= rank)
-    if (tid < K) prefix[tid] = 0;
+    // ---- 4. running sums in front of every chunk of 64 sorted weights
+    const int nchunks = (n_dense + 63) / 64;
+    for (int c = wave; c < nchunks; c += T / 64) {
+        const int j = c * 64 + lane;
+        u64 s0 = 0, lo = 0, hi = 0;
+        if (j < n_dense) {
+            const u32 v = A[j];
+            s0 = v & 0xFFFFu;
+            const i64 p = (i64)s0 * half_to_fixed(key_half(v >> 16));
+            lo = (u64)p & 0xFFFFFFFFull; hi = (u64)(p >> 32);
+        }
+        s0 = wave_sum_all(s0); lo = wave_sum_all(lo); hi = wave_sum_all(hi);
+        if (lane == 0) { c0[c + 1] = s0; clo[c + 1] = lo; chi[c + 1] = hi; }
+    }
     __syncthreads();
+    if (tid == 0) {
+        u64 r0 = 0, rl = 0, rh = 0;
+        c0[0] = 0; clo[0] = 0; chi[0] = 0;
+        for (int c = 1; c <= nchunks; ++c) { r0 += c0[c]; rl += clo[c]; rh += chi[c]; c0[c] = r0; clo[c] = rl; chi[c] = rh; }
+    }
+    // ---- 5. equal-count start
+    if (tid < K) {
+        const u64 rank = ((u64)(2 * tid + 1) * (u64)n_dense) / (u64)(2 * K);
+        cen[tid] = n_dense > 0 ? half_bits_to_f32(key_half(A[rank] >> 16)) : 0.f;
+    }
+    if (tid <= K) prevpos[tid] = -1;
+    __syncthreads();
+
+    // ---- 6. Lloyd iterations on the boundaries
+    int it = 0;
     if (n_dense > 0) {
-        for (int bit = 15; bit >= 0; --bit) {
-            u32 cand[K];
-            int cnt[K];
-#pragma unroll
-            for (int k = 0; k < K; ++k) { cand[k] = prefix[k] | (1u << bit); cnt[k] = 0; }
-            for (int j = tid; j < N; j += T) {
-                if (il[j] != 0xFF) {
-                    const u32 key = half_key(wl[j]);
-#pragma unroll
-                    for (int k = 0; k < K; ++k) cnt[k] += key < cand[k];
+        for (;;) {
+            if (tid < K - 1) thr2[tid] = __fadd_rn(cen[tid], cen[tid + 1]);
+            if (tid == 0) flag = 0;
+            __syncthreads();
+            for (int k = wave; k < K - 1; k += T / 64) {                 // uniform per wave
+                const float t = thr2[k];
+                // p = #{ j < n_dense : 2 w_j <= t }: rounds of 64 probes; invariant: the answer lies in [lo, lo + len]
+                int lo = 0, len = n_dense;
+                while (len > 0) {
+                    const int step = (len + 63) / 64;                    // probe positions lo + step (l + 1) - 1
+                    const int j = lo + step * (lane + 1) - 1;
+                    bool le = false;
+                    if (j < lo + len) le = !(t < 2.0f * half_bits_to_f32(key_half(A[j] >> 16)));
+                    const int cnt = __builtin_popcountll(__ballot(le));  // probes with 2 w <= t form a prefix
+                    lo += cnt * step;
+                    len = min(step - 1, n_dense - lo);                   // the next probe after the prefix is > t (or past the end)
+                    if (len < 0) len = 0;
+                }
+                const int p = lo;
+                const int c = p >> 6, inside = p & 63;
+                u64 s0 = 0, l = 0, h = 0;
+                if (lane < inside) {
+                    const u32 v = A[c * 64 + lane];
+                    s0 = v & 0xFFFFu;
+                    const i64 pr = (i64)s0 * half_to_fixed(key_half(v >> 16));
+                    l = (u64)pr & 0xFFFFFFFFull; h = (u64)(pr >> 32);
+                }
+                s0 = wave_sum_all(s0); l = wave_sum_all(l); h = wave_sum_all(h);
+                if (lane == 0) {
+                    pos[k + 1] = p; F0[k + 1] = c0[c] + s0; Flo[k + 1] = clo[c] + l; Fhi[k + 1] = chi[c] + h;
+                    if (p != prevpos[k + 1]) flag = 1;
                 }
             }
-#pragma unroll
-            for (int k = 0; k < K; ++k) {
-                const int tot = wave_sum_all(cnt[k]);
-                if (lane == 0) atomicAdd(&counts[k], tot);
+            if (tid == 0) {
+                pos[0] = 0; F0[0] = 0; Flo[0] = 0; Fhi[0] = 0;
+                pos[K] = n_dense; F0[K] = c0[nchunks]; Flo[K] = clo[nchunks]; Fhi[K] = chi[nchunks];
             }
             __syncthreads();
-            if (tid < K) {
-                const u64 rank = ((u64)(2 * tid + 1) * (u64)n_dense) / (u64)(2 * K);
-                if ((u64)counts[tid] <= rank) prefix[tid] |= 1u << bit;
-                counts[tid] = 0;
+            const bool stop = flag == 0 || it == max_iter;
+            if (!stop && tid < K) {
+                const u64 s0 = F0[tid + 1] - F0[tid];
+                if (s0 > 0) {
+                    const double s1 = (double)(i64)(Fhi[tid + 1] - Fhi[tid]) * 4294967296.0 + (double)(Flo[tid + 1] - Flo[tid]);
+                    cen[tid] = (float)(s1 * 5.9604644775390625e-08 / (double)s0);
+                }
             }
+            if (tid <= K) prevpos[tid] = pos[tid];
             __syncthreads();
+            if (stop) break;
+            ++it;
         }
     }
-    if (tid < K) cen[tid] = n_dense > 0 ? half_bits_to_f32(key_half(prefix[tid])) : 0.f;
-    if (tid == 0) { flags[0] = 0; flags[1] = 0; }
-    __syncthreads();
 
-    // ---- 4. Lloyd iterations
-    int it = 0;
-    for (;;) {
-        if (tid < K - 1) thr2[tid] = __fadd_rn(cen[tid], cen[tid + 1]);
-        __syncthreads();
-        float t[K - 1];
-#pragma unroll
-        for (int k = 0; k < K - 1; ++k) t[k] = thr2[k];
-        int changed = 0;
-        for (int j = tid; j < N; j += T) {
-            const u32 old = il[j];
-            if (old != 0xFF) {
-                const u32 wb = wl[j];
-                const float two_w = 2.0f * half_bits_to_f32(wb);
-                u32 a = 0;
-#pragma unroll
-                for (int k = 0; k < K - 1; ++k) a += t[k] < two_w;
-                changed |= a != old;
-                il[j] = (uint8_t)a;
-                const u64 sv = sl[j];
-                const i64 p = (i64)sv * half_to_fixed(wb);
-                atomicAdd(&S0[a], sv);
-                atomicAdd(&S1lo[a], (u64)p & 0xFFFFFFFFull);
-                atomicAdd(&S1hi[a], (u64)(p >> 32));
-            }
-        }
-        if (changed) flags[it & 1] = 1;                              // benign race: every writer stores 1
-        __syncthreads();
-        const bool any_changed = flags[it & 1] != 0;
-        const bool stop = !any_changed || it == max_iter;
-        if (!stop && tid < K) {
-            if (S0[tid] > 0) {
-                const double s1 = (double)(i64)S1hi[tid] * 4294967296.0 + (double)S1lo[tid];
-                cen[tid] = (float)(s1 * 5.9604644775390625e-08 / (double)S0[tid]);
-            }
-        }
-        if (tid < K) { S0[tid] = 0; S1lo[tid] = 0; S1hi[tid] = 0; }
-        if (tid == 0) flags[(it + 1) & 1] = 0;
-        __syncthreads();
-        if (stop) break;
-        ++it;
-    }
-
-    // ---- 5. fp16 tables and final indices
+    // ---- 7. fp16 tables; final indices from the row as it lies in memory, packed 32 per thread
     if (tid < K) {
         const uint16_t hb = __builtin_bit_cast(uint16_t, (_Float16)cen[tid]);
         lut[(size_t)row * K + tid] = hb;
@@ -328,32 +380,30 @@ __global__ void __launch_bounds__(256) quant_kmeans_kernel(int M, int N, int max
             const i64 a = cfix[k] < 0 ? -cfix[k] : cfix[k];
             if (a < best) { best = a; zero = k; }
         }
-        for (int j = tid; j < N; j += T) {
-            u32 a = zero;
-            if (il[j] != 0xFF) {
-                const i64 w2 = 2 * half_to_fixed(wl[j]);
-                a = 0;
-#pragma unroll
-                for (int k = 0; k < K - 1; ++k) a += tf[k] < w2;
-            }
-            il[j] = (uint8_t)a;
-        }
-    }
-    __syncthreads();
-
-    // ---- 6. packed index stream: element j owns bits [j b, j b + b) of the row, least significant bit first
-    {
         u32* out = static_cast<u32*>(qidx) + (size_t)row * ((size_t)N * BITS / 32);
         for (int ch = tid; ch < N / 32; ch += T) {
             u32 q[BITS];
 #pragma unroll
             for (int k = 0; k < BITS; ++k) q[k] = 0;
 #pragma unroll
-            for (int e = 0; e < 32; ++e) {
-                const u32 v = il[ch * 32 + e];
-                const int bitpos = e * BITS;
-                q[bitpos >> 5] |= v << (bitpos & 31);
-                if ((bitpos & 31) + BITS > 32) q[(bitpos >> 5) + 1] |= v >> (32 - (bitpos & 31));
+            for (int g = 0; g < 4; ++g) {
+                const u32x4 wv = reinterpret_cast<const u32x4*>(wrow + ch * 32)[g], sv = reinterpret_cast<const u32x4*>(srow + ch * 32)[g];
+                const u32 wd[4] = {wv.x, wv.y, wv.z, wv.w}, sd[4] = {sv.x, sv.y, sv.z, sv.w};
+#pragma unroll
+                for (int e8 = 0; e8 < 8; ++e8) {
+                    const u32 wb = (e8 & 1) ? wd[e8 >> 1] >> 16 : wd[e8 >> 1] & 0xFFFFu;
+                    const u32 sb = (e8 & 1) ? sd[e8 >> 1] >> 16 : sd[e8 >> 1] & 0xFFFFu;
+                    u32 a = zero;
+                    if (!is_extracted(wb, sb, key_min, key_max, s_thr)) {
+                        const i64 w2 = 2 * half_to_fixed(wb);
+                        a = 0;
+#pragma unroll
+                        for (int k = 0; k < K - 1; ++k) a += tf[k] < w2;
+                    }
+                    const int e = g * 8 + e8, bitpos = e * BITS;
+                    q[bitpos >> 5] |= a << (bitpos & 31);
+                    if ((bitpos & 31) + BITS > 32) q[(bitpos >> 5) + 1] |= a >> (32 - (bitpos & 31));
+                }
             }
 #pragma unroll
             for (int k = 0; k < BITS; ++k) out[(size_t)ch * BITS + k] = q[k];
@@ -371,24 +421,26 @@ hipError_t launch_quantize(const QuantArgs& a, hipStream_t s) {
     const int hist_blocks = (int)min((long long)2048, (units + 255) / 256);
     hipLaunchKernelGGL(quant_clear_kernel, dim3(4), dim3(256), 0, s, ws);
     hipLaunchKernelGGL(quant_hist1_kernel, dim3(hist_blocks), dim3(256), 0, s, units, static_cast<const u32x4*>(a.w), static_cast<const u32x4*>(a.sens), ws);
-    hipLaunchKernelGGL(quant_select1_kernel, dim3(1), dim3(64), 0, s, total, (u64)a.n_lo, (u64)a.n_hi, (u64)a.n_sens, ws);
+    hipLaunchKernelGGL(quant_select1_kernel, dim3(1), dim3(256), 0, s, total, (u64)a.n_lo, (u64)a.n_hi, (u64)a.n_sens, ws);
     hipLaunchKernelGGL(quant_hist2_kernel, dim3(hist_blocks), dim3(256), 0, s, units, static_cast<const u32x4*>(a.w), static_cast<const u32x4*>(a.sens), ws);
-    hipLaunchKernelGGL(quant_select2_kernel, dim3(1), dim3(64), 0, s, ws);
+    hipLaunchKernelGGL(quant_select2_kernel, dim3(1), dim3(256), 0, s, ws);
     hipLaunchKernelGGL(quant_count_kernel, dim3((a.M + 3) / 4), dim3(256), 0, s, a.M, a.N, static_cast<const uint16_t*>(a.w), static_cast<const uint16_t*>(a.sens), ws, a.rowptr);
     hipLaunchKernelGGL(quant_scan_kernel, dim3(1), dim3(1024), 0, s, a.M, a.rowptr);
-    const size_t lds = (size_t)a.N * 5;
+    int NP = 128;
+    while (NP < a.N) NP <<= 1;
+    const size_t lds = (size_t)NP * 4 + (size_t)(NP / 64 + 1) * 24;
     hipError_t e = hipSuccess;
     if (a.bits == 3) {
         static bool enabled = false;
         if (!enabled) { e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_kmeans_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024); enabled = true; }
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((quant_kmeans_kernel<3>), dim3(a.M), dim3(256), lds, s, a.M, a.N, a.max_iter, static_cast<const uint16_t*>(a.w), static_cast<const uint16_t*>(a.sens),
+        hipLaunchKernelGGL((quant_kmeans_kernel<3>), dim3(a.M), dim3(256), lds, s, a.M, a.N, NP, a.max_iter, static_cast<const uint16_t*>(a.w), static_cast<const uint16_t*>(a.sens),
                            ws, a.rowptr, a.qidx, static_cast<uint16_t*>(a.lut), a.cols, static_cast<uint16_t*>(a.vals), a.iters);
     } else {
         static bool enabled = false;
         if (!enabled) { e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_kmeans_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024); enabled = true; }
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((quant_kmeans_kernel<4>), dim3(a.M), dim3(256), lds, s, a.M, a.N, a.max_iter, static_cast<const uint16_t*>(a.w), static_cast<const uint16_t*>(a.sens),
+        hipLaunchKernelGGL((quant_kmeans_kernel<4>), dim3(a.M), dim3(256), lds, s, a.M, a.N, NP, a.max_iter, static_cast<const uint16_t*>(a.w), static_cast<const uint16_t*>(a.sens),
                            ws, a.rowptr, a.qidx, static_cast<uint16_t*>(a.lut), a.cols, static_cast<uint16_t*>(a.vals), a.iters);
     }
     return hipGetLastError();
