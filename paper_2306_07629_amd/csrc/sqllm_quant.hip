@@ -10,7 +10,8 @@
 //   3. Per output row, weighted 1-D k-means over the remaining weights (Eq. 4: minimise sum_j s_j (w_j - Q(w_j))^2
 //      over 2^b values) by Lloyd iterations: equal-count start, nearest-centroid assignment, sensitivity-weighted
 //      means.  Every integer decision is taken in fp32 exactly as written below and the weighted sums are exact
-//      64-bit integers (LDS integer atomics), so the result does not depend on the order of the additions.
+//      64-bit integers, so the result does not depend on the order of the additions.  The row is sorted once and
+//      the iterations move the K - 1 cluster boundaries (see quant_kmeans_kernel).
 //   4. fp16 tables, final indices (nearest table entry in exact arithmetic, ties to the lower index; an extracted
 //      position gets the entry nearest to zero) and the packed index stream in the layout the matvec reads.
 #include <hip/hip_runtime.h>
