@@ -9,6 +9,7 @@ import oracle
 from oracle import numpy_route as nr
 
 LLAMA7B_BLOCK = [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)]
+LLAMA13B_BLOCK = [(5120, 5120)] * 4 + [(13824, 5120)] * 2 + [(5120, 13824)]
 
 
 def storage_bits(M, N, bits, nnz, count_rowptr):
@@ -27,12 +28,16 @@ def test_average_bits_match_paper_table(golden_dir):
             continue
         bits, frac, avg_printed, comp_printed = [float(s) for s in line.split("|")]
         bits = int(bits)
-        total_w = sum(M * N for M, N in LLAMA7B_BLOCK)
+        block = LLAMA13B_BLOCK if bits == 2 else LLAMA7B_BLOCK        # the 2-bit lines are the 13B column of App. F
+        total_w = sum(M * N for M, N in block)
         for count_rowptr in (False, True):
-            tot = sum(storage_bits(M, N, bits, gen._load().sqgen_nnz(M, N, frac), count_rowptr) for M, N in LLAMA7B_BLOCK)
+            tot = sum(storage_bits(M, N, bits, gen._load().sqgen_nnz(M, N, frac), count_rowptr) for M, N in block)
             avg = tot / total_w
-            assert abs(avg - avg_printed) < 0.011, (bits, frac, avg)
-            assert abs(16 / avg - comp_printed) < 0.015, (bits, frac, 16 / avg)
+            assert abs(avg - avg_printed) < (0.016 if bits == 2 and count_rowptr else 0.011), (bits, frac, avg)
+            if bits != 2:                                              # App. F prints no compression rate
+                assert abs(16 / avg - comp_printed) < 0.015, (bits, frac, 16 / avg)
+        if bits == 2:
+            continue
         # alternatives the table rules out: 16-bit columns, fp32 tables
         if frac:
             alt = sum(M * N * bits + M * (1 << bits) * 16 + gen._load().sqgen_nnz(M, N, frac) * 32 for M, N in LLAMA7B_BLOCK) / total_w
@@ -51,7 +56,7 @@ def test_algorithmic_bytes_formula():
 
 
 @pytest.mark.parametrize("bits,skew,frac", [(3, (0.1, 0.5), 0.0045), (4, None, 0.0045), (3, (0.01, 0.3), 0.0045),
-                                            (4, (0.1, 0.5), 0.01), (3, None, 0.0005), (3, None, 0.0)])
+                                            (4, (0.1, 0.5), 0.01), (3, None, 0.0005), (3, None, 0.0), (2, (0.1, 0.5), 0.0045), (2, None, 0.001)])
 def test_layer_invariants(bits, skew, frac):
     M, N = 600, 1024
     L = gen.make_layer(M, N, bits, frac=frac, skew=skew, B=1, seed=77, keep_debug=True)
