@@ -27,6 +27,8 @@ WORKLOADS = {
     # name: (list of (M, N), bits, frac, skew, B)
     "llama7b_mlp_pair_3bit": ([(11008, 4096), (4096, 11008)], 3, 0.0045, (0.10, 0.50), 1),
     "llama7b_mlp_pair_4bit": ([(11008, 4096), (4096, 11008)], 4, 0.0045, (0.10, 0.50), 1),
+    "llama7b_mlp_pair_2bit": ([(11008, 4096), (4096, 11008)], 2, 0.0045, (0.10, 0.50), 1),
+    "llama7b_mlp_pair_2bit_sparse0.1": ([(11008, 4096), (4096, 11008)], 2, 0.001, (0.10, 0.50), 1),
     "single_4096_4bit": ([(4096, 4096)], 4, 0.0045, None, 1),
     "llama13b_attn_3bit": ([(5120, 5120)], 3, 0.0045, None, 1),
     "llama13b_attn_4bit": ([(5120, 5120)], 4, 0.0045, None, 1),
@@ -297,8 +299,7 @@ def main():
                "gbs": step_bytes / med / 1e9}
 
     out = {
-        "metric": "us per dense+sparse matvec (3-bit LUT + 0.45% CSR), effective HBM GB/s in roofline" if bits == 3
-                  else "us per dense+sparse matvec (4-bit LUT + 0.45% CSR), effective HBM GB/s in roofline",
+        "metric": f"us per dense+sparse matvec ({bits}-bit LUT + {100 * frac:g}% CSR), effective HBM GB/s in roofline",
         "value": us_per_matvec, "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec_cold / args.steps * 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",

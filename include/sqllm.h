@@ -5,10 +5,11 @@
  *
  *        Y = D X + S X                                   (paper Sec. 4.2: W = D + S, W X = D X + S X)
  *
- *   D  (M x N)  dense part, stored as b-bit indices (b = 3 or 4) into ONE look-up table of 2^b fp16
+ *   D  (M x N)  dense part, stored as b-bit indices (b = 2, 3 or 4) into ONE look-up table of 2^b fp16
  *               values PER OUTPUT ROW:  D[i][j] = lut[i][ idx(i,j) ]
  *               (Sec. 4.3 "the compressed matrices store 3/4-bit indices, which correspond to LUT entries
- *               containing FP16 values"; Sec. 5 "each output channel is assigned a separate lookup table").
+ *               containing FP16 values"; Sec. 5 "each output channel is assigned a separate lookup table";
+ *               App. F quantises to 2 bits with the same format).
  *   S  (M x N)  sparse part in compressed-sparse-row form with fp16 values (Sec. 4.2: outliers and
  *               sensitive values kept in FP16 and stored in CSR).
  *   X  (N x B)  fp16 activations, B = 1..8 vectors;  Y (M x B) fp16.
@@ -17,7 +18,7 @@
  *   qidx   row i is a little-endian bit stream of N*b bits starting at byte i*N*b/8.  Element j owns stream
  *          bits [j*b, j*b+b), least-significant bit first; stream bit k is bit (k mod 8) of byte (k div 8).
  *          Rows follow each other without padding.  N must be a multiple of 128, so a row is a whole number
- *          of 48-byte (b=3) or 64-byte (b=4) groups of 128 elements.
+ *          of 32-byte (b=2), 48-byte (b=3) or 64-byte (b=4) groups of 128 elements.
  *   lut    fp16 [M][2^b], row-major.  No ordering of the entries is assumed.
  *   rowptr int32 [M+1], rowptr[0] = 0, non-decreasing, rowptr[M] = nnz.
  *   cols   int32 [nnz], 0 <= cols[p] < N.   vals  fp16 [nnz].  Duplicate (row, col) entries add up.
@@ -51,7 +52,7 @@ extern "C" {
 typedef enum {
     SQLLM_OK = 0,
     SQLLM_ERR_NULL = 1,   /* a required pointer is NULL                                   */
-    SQLLM_ERR_BITS = 2,   /* bits is not 3 or 4                                           */
+    SQLLM_ERR_BITS = 2,   /* bits is not 2, 3 or 4                                        */
     SQLLM_ERR_SHAPE = 3,  /* M < 0, N <= 0, N % 128 != 0, or N > SQLLM_MAX_N              */
     SQLLM_ERR_ALIGN = 4,  /* a pointer violates the alignment rules above                 */
     SQLLM_ERR_NNZ = 5,    /* nnz < 0 or nnz >= 2^31                                       */

@@ -34,7 +34,7 @@ int check_shape(int M, int N, int B) {
 }
 
 int check_bits(int bits) {
-    if (bits != 3 && bits != 4) return fail(SQLLM_ERR_BITS, "bits = %d, only 3 and 4 are supported", bits);
+    if (bits < 2 || bits > 4) return fail(SQLLM_ERR_BITS, "bits = %d, only 2, 3 and 4 are supported", bits);
     return SQLLM_OK;
 }
 

@@ -12,6 +12,7 @@
 //   * Dequantisation goes through PAIR TABLES in LDS: for every row of the block the workgroup first builds
 //       b = 3:  64 entries,  entry (a | c << 3) = (lut[a], lut[c]) as two fp16 in one dword   (256 B / row)
 //       b = 4: 256 entries,  entry (a | c << 4) = (lut[a], lut[c])                            (1 KB / row)
+//       b = 2: 256 entries,  entry (a | c << 2 | d << 4 | f << 6) = (lut[a], lut[c], lut[d], lut[f]), 8 bytes  (2 KB / row)
 //     so ONE ds_read_b32, addressed by a 6- or 8-bit field of the index stream (two neighbouring indices),
 //     returns a ready-made fp16 pair for v_dot2_f32_f16 (two products, fp32 accumulate).  Measured on MI355X
 //     a wave-wide look-up occupies the LDS for ~4 cycles (64 entries) / ~7 cycles (256 entries, bank
@@ -37,6 +38,7 @@ typedef _Float16 half_t;
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32;
 typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+typedef u32 u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWave = 64;
 constexpr int kLaneElems = 32;                      // indices per lane per row
@@ -110,18 +112,42 @@ __device__ __forceinline__ void pair_offsets(const LaneChunk<4>& c, u32 (&a)[16]
 #pragma unroll
     for (int p = 0; p < 16; ++p) a[p] = ((c.q[p >> 2] >> (8 * (p & 3))) & 0xFF) << 2;
 }
+//   b = 2: FOUR indices are one byte of the 64-bit chunk; the table entry is 8 bytes (four fp16), 8 look-ups per lane
+__device__ __forceinline__ void pair_offsets(const LaneChunk<2>& c, u32 (&a)[16]) {
+#pragma unroll
+    for (int p = 0; p < 8; ++p) a[p] = ((c.q[p >> 2] >> (8 * (p & 3))) & 0xFF) << 3;
+#pragma unroll
+    for (int p = 8; p < 16; ++p) a[p] = 0;
+}
 
 template <int BITS>
 struct TableShape {
-    static constexpr int kEntryBits = 2 * BITS;               // 6 or 8
-    static constexpr int kEntries = 1 << kEntryBits;          // 64 or 256
-    static constexpr int kRowBytes = 2 << BITS;               // bytes of one row's fp16 table: 16 or 32
+    static constexpr int kGroup = BITS == 2 ? 4 : 2;          // weights returned by one look-up
+    static constexpr int kEntryBits = kGroup * BITS;          // 8, 6 or 8
+    static constexpr int kEntries = 1 << kEntryBits;          // 256, 64 or 256
+    static constexpr int kEntryDwords = kGroup / 2;           // 2, 1 or 1
+    static constexpr int kTableDwords = kEntries * kEntryDwords;   // LDS dwords of one row's table
+    static constexpr int kRowBytes = 2 << BITS;               // bytes of one row's fp16 table: 8, 16 or 32
+    static constexpr int kRawUnit = kRowBytes < 16 ? kRowBytes : 16;   // bytes of fp16 table one lane fetches
 };
 
 // Pair tables of R rows from their fp16 tables staged in LDS (raw[u << BITS | k]); executed by ONE wave.
 template <int BITS, int R>
 __device__ __forceinline__ void build_tables(u32* __restrict__ tables, const uint16_t* __restrict__ raw, int lane) {
     constexpr int E = TableShape<BITS>::kEntries, K = 1 << BITS;
+    if constexpr (BITS == 2) {
+        // entry (a | c << 2 | d << 4 | f << 6) = (lut[a], lut[c], lut[d], lut[f]); lane l writes entries l, l + 64, ...
+#pragma unroll
+        for (int u = 0; u < R; ++u) {
+            const u32 v0 = raw[u * K + (lane & 3)], v1 = raw[u * K + ((lane >> 2) & 3)], v2 = raw[u * K + ((lane >> 4) & 3)];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const u32 v3 = raw[u * K + i];
+                *reinterpret_cast<u32x2*>(tables + (u * E + 64 * i + lane) * 2) = u32x2{v0 | (v1 << 16), v2 | (v3 << 16)};
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int u = 0; u < R; ++u) {
         const u32 lo = raw[u * K + (lane & (K - 1))];           // the same for all entries of this lane
@@ -224,8 +250,16 @@ __device__ __forceinline__ void lookup_chunk(const LaneChunk<BITS>& c, const u32
     u32 a[16];
     pair_offsets(c, a);
     const char* tb = reinterpret_cast<const char*>(table);
+    if constexpr (BITS == 2) {
 #pragma unroll
-    for (int p = 0; p < 16; ++p) w[p] = *reinterpret_cast<const u32*>(tb + a[p]);
+        for (int p = 0; p < 8; ++p) {
+            const u32x2 v = *reinterpret_cast<const u32x2*>(tb + a[p]);
+            w[2 * p] = v.x; w[2 * p + 1] = v.y;
+        }
+    } else {
+#pragma unroll
+        for (int p = 0; p < 16; ++p) w[p] = *reinterpret_cast<const u32*>(tb + a[p]);
+    }
 }
 
 // 16 * NB packed dot products (two fp16 products each, fp32 accumulate); two accumulator chains per column
@@ -440,9 +474,11 @@ template <int BITS, int NB, int R, int D, int MAXT, int XG>
 __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
     static_assert(D >= 2 && D <= R, "prefetch depth");
     constexpr int E = TableShape<BITS>::kEntries, K = 1 << BITS;
-    constexpr int kRawLanes = R * TableShape<BITS>::kRowBytes / 16;  // lanes that fetch 16 bytes of fp16 tables
+    constexpr int kRawUnit = TableShape<BITS>::kRawUnit;             // bytes of fp16 tables one lane fetches (16, or 8 for b = 2)
+    constexpr int kRawLanes = R * TableShape<BITS>::kRowBytes / kRawUnit;
     constexpr int UB = 8;                                            // sparse batches per wave and round
-    __shared__ u32 tables[R * E];
+    constexpr int TD = TableShape<BITS>::kTableDwords;
+    __shared__ __align__(8) u32 tables[R * TD];
     __shared__ __align__(16) uint16_t raw[R * K];
     __shared__ float part[kMaxDenseWaves * 4 * R * NB];              // dense:  [wave][16-lane row][r][t]
     __shared__ float spart[(kMaxDenseWaves + 1) * R * NB];           // sparse: [wave][r][t]
@@ -468,10 +504,15 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
         // ---- dense wave.  Issue order: (wave 0: fp16 tables), activations, first D rows of the index stream.
         u32x4 rawv = {0, 0, 0, 0};
         if (wave == 0 && lane < kRawLanes) {
-            const int u = lane * 16 / TableShape<BITS>::kRowBytes;
+            const int u = lane * kRawUnit / TableShape<BITS>::kRowBytes;
             const int row = min(r0 + u, g.M - 1);
-            const char* src = static_cast<const char*>(g.lut) + (size_t)row * TableShape<BITS>::kRowBytes + (lane * 16) % TableShape<BITS>::kRowBytes;
-            rawv = *reinterpret_cast<const u32x4*>(src);
+            const char* src = static_cast<const char*>(g.lut) + (size_t)row * TableShape<BITS>::kRowBytes + (lane * kRawUnit) % TableShape<BITS>::kRowBytes;
+            if constexpr (kRawUnit == 16) {
+                rawv = *reinterpret_cast<const u32x4*>(src);
+            } else {
+                const u32x2 v = *reinterpret_cast<const u32x2*>(src);
+                rawv.x = v.x; rawv.y = v.y;
+            }
         }
         const int j0 = wave * kSliceCols + lane * kLaneElems;
         const bool live = j0 < g.N;
@@ -491,7 +532,10 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
                 for (int p = 0; p < 16; ++p) xr[t][p] = 0;
         }
         if (wave == 0) {
-            if (lane < kRawLanes) *reinterpret_cast<u32x4*>(raw + lane * 8) = rawv;
+            if (lane < kRawLanes) {
+                if constexpr (kRawUnit == 16) *reinterpret_cast<u32x4*>(raw + lane * 8) = rawv;
+                else *reinterpret_cast<u32x2*>(raw + lane * 4) = u32x2{rawv.x, rawv.y};
+            }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -507,7 +551,7 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
 #pragma unroll
         for (int u = 0; u < R; ++u) {
             if (u + 1 < R) {
-                lookup_chunk<BITS>(c[u + 1], tables + (u + 1) * E, w[(u + 1) & 1]);
+                lookup_chunk<BITS>(c[u + 1], tables + (u + 1) * TD, w[(u + 1) & 1]);
                 if (u + 1 + D < R) c[(u + 1 + D) % R] = load_chunk<BITS>(qlane + (size_t)min(r0 + u + 1 + D, g.M - 1) * row_dwords);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -592,9 +636,9 @@ __global__ void __launch_bounds__(256) csr_rowwise_kernel(MatvecArgs g) {
 // look-up returns the indices themselves.
 template <int BITS>
 __global__ void __launch_bounds__(64) decode_kernel(int M, int N, const void* qidx, const void* lut, void* idx_out, void* w_out) {
-    constexpr int E = TableShape<BITS>::kEntries, K = 1 << BITS;
-    __shared__ u32 table[E];
-    __shared__ __align__(16) uint16_t raw[K];
+    constexpr int K = 1 << BITS;
+    __shared__ __align__(8) u32 table[TableShape<BITS>::kTableDwords];
+    __shared__ __align__(16) uint16_t raw[K < 8 ? 8 : K];
     const int lane = threadIdx.x;
     const int row = blockIdx.y, slice = blockIdx.x;
     const int j0 = slice * kSliceCols + lane * kLaneElems;
@@ -607,12 +651,8 @@ __global__ void __launch_bounds__(64) decode_kernel(int M, int N, const void* qi
     __syncthreads();
     build_tables<BITS, 1>(table, raw, lane);
     __syncthreads();
-    u32 a[16];
-    pair_offsets(c, a);
     u32 w[16];
-    const char* tb = reinterpret_cast<const char*>(table);
-#pragma unroll
-    for (int k = 0; k < 16; ++k) w[k] = *reinterpret_cast<const u32*>(tb + a[k]);
+    lookup_chunk<BITS>(c, table, w);
     if (!live) return;
     if (idx_out) {
         uint8_t* o = static_cast<uint8_t*>(idx_out) + (size_t)row * N + j0;
@@ -731,7 +771,7 @@ static hipError_t launch_matvec_b(const MatvecArgs& g0, hipStream_t s) {
 }
 
 hipError_t launch_matvec(const MatvecArgs& g, hipStream_t s) {
-    return g.bits == 3 ? launch_matvec_b<3>(g, s) : launch_matvec_b<4>(g, s);
+    return g.bits == 2 ? launch_matvec_b<2>(g, s) : (g.bits == 3 ? launch_matvec_b<3>(g, s) : launch_matvec_b<4>(g, s));
 }
 
 hipError_t launch_csr_rowwise(const MatvecArgs& g0, hipStream_t s) {
@@ -755,7 +795,8 @@ hipError_t launch_decode(int M, int N, int bits, const void* qidx, const void* l
         const void* l = lut ? static_cast<const char*>(lut) + (size_t)m0 * (1 << bits) * 2 : nullptr;
         void* io = idx_out ? static_cast<char*>(idx_out) + (size_t)m0 * N : nullptr;
         void* wo = w_out ? static_cast<char*>(w_out) + (size_t)m0 * N * 2 : nullptr;
-        if (bits == 3) hipLaunchKernelGGL((decode_kernel<3>), dim3(slices, m), dim3(kWave), 0, s, m, N, q, l, io, wo);
+        if (bits == 2) hipLaunchKernelGGL((decode_kernel<2>), dim3(slices, m), dim3(kWave), 0, s, m, N, q, l, io, wo);
+        else if (bits == 3) hipLaunchKernelGGL((decode_kernel<3>), dim3(slices, m), dim3(kWave), 0, s, m, N, q, l, io, wo);
         else hipLaunchKernelGGL((decode_kernel<4>), dim3(slices, m), dim3(kWave), 0, s, m, N, q, l, io, wo);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

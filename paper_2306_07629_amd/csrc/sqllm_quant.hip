@@ -431,7 +431,13 @@ hipError_t launch_quantize(const QuantArgs& a, hipStream_t s) {
     while (NP < a.N) NP <<= 1;
     const size_t lds = (size_t)NP * 4 + (size_t)(NP / 64 + 1) * 24;
     hipError_t e = hipSuccess;
-    if (a.bits == 3) {
+    if (a.bits == 2) {
+        static bool enabled = false;
+        if (!enabled) { e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_kmeans_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024); enabled = true; }
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((quant_kmeans_kernel<2>), dim3(a.M), dim3(256), lds, s, a.M, a.N, NP, a.max_iter, static_cast<const uint16_t*>(a.w), static_cast<const uint16_t*>(a.sens),
+                           ws, a.rowptr, a.qidx, static_cast<uint16_t*>(a.lut), a.cols, static_cast<uint16_t*>(a.vals), a.iters);
+    } else if (a.bits == 3) {
         static bool enabled = false;
         if (!enabled) { e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_kmeans_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024); enabled = true; }
         if (e != hipSuccess) return e;

@@ -41,7 +41,7 @@ def expect(status_name, fn, *args):
 
 def test_lut_gemv_argument_errors():
     f = sq.sqllm_lut_gemv
-    expect("SQLLM_ERR_BITS", f, 4, 128, 2, 1, A, A, A, A)
+    expect("SQLLM_ERR_BITS", f, 4, 128, 1, 1, A, A, A, A)
     expect("SQLLM_ERR_BITS", f, 4, 128, 5, 1, A, A, A, A)
     expect("SQLLM_ERR_SHAPE", f, -1, 128, 3, 1, A, A, A, A)
     expect("SQLLM_ERR_SHAPE", f, 4, 0, 3, 1, A, A, A, A)

@@ -31,8 +31,15 @@ def check_y(y_gpu, y_ref, absdot, N, what=""):
 
 
 SMALL = [  # (M, N, bits, frac, skew, B)  — several 2048-column slices, ragged last slice, ragged row blocks
+    (37, 128, 2, 0.0, None, 1),
     (37, 128, 3, 0.0, None, 1),
     (37, 128, 4, 0.0, None, 1),
+    (301, 2176, 2, 0.0045, (0.1, 0.5), 1),
+    (130, 4096, 2, 0.001, None, 1),
+    (67, 11008, 2, 0.0045, (0.1, 0.5), 1),
+    (33, 22016, 2, 0.0045, (0.01, 0.3), 1),
+    (65, 8192, 2, 0.0045, (0.01, 0.3), 4),
+    (65, 2304, 2, 0.0045, None, 3),
     (301, 2048, 3, 0.0045, (0.1, 0.5), 1),
     (301, 2176, 4, 0.0045, (0.1, 0.5), 1),
     (130, 4096, 3, 0.0045, None, 1),

@@ -37,6 +37,8 @@ def compare(M, N, bits, got, ref, rows=None):
 
 
 CASES = [  # (M, N, bits, outlier_frac, sens_frac, max_iter)
+    (33, 128, 2, 0.001, 0.0005, 20),
+    (50, 4096, 2, 0.0005, 0.0005, 40),      # the 2-bit + 0.1 % setting of App. F
     (33, 128, 3, 0.0, 0.0, 20),
     (33, 128, 4, 0.004, 0.0005, 20),
     (70, 512, 3, 0.004, 0.0005, 50),

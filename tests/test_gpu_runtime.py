@@ -97,7 +97,7 @@ def test_inputs_at_the_very_end_of_an_allocation():
     rows are clamped, never read past the end); checked for correctness of the result"""
     import torch
     import paper_2306_07629_amd as sq
-    for bits, M, N in [(3, 5, 2176), (4, 3, 128), (3, 2, 28672)]:
+    for bits, M, N in [(3, 5, 2176), (4, 3, 128), (3, 2, 28672), (2, 5, 2176), (2, 1, 128)]:
         L = gen.make_layer(M, N, bits, frac=0.0045, seed=60 + M)
         D = sq.DeviceLayer(L)          # torch allocates each array exactly as large as its contents
         y = _f64(D.matvec())
