@@ -86,6 +86,7 @@ int run_matvec(int M, int N, int bits, long long nnz, int B, const void* qidx, c
     g.qidx = qidx; g.lut = lut; g.rowptr = rowptr; g.cols = cols; g.vals = vals; g.x = x; g.y = y;
     const int waves = qidx ? (N + 2047) / 2048 + (nnz > 0 ? 1 : 0) : 4;
     g.rows_per_wg = pick_rows(M, waves);
+    g.mfma_batch = g_rows_per_wg == 0;       // an explicit rows-per-workgroup request selects the vector-ALU kernels
     const hipError_t e = sqllm::launch_matvec(g, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "matvec launch");
     return SQLLM_OK;

@@ -9,6 +9,7 @@ struct MatvecArgs {
     int bt0, bn;            // batch columns [bt0, bt0 + bn) are computed by this launch (bn <= 4)
     int rows_per_wg;        // requested rows per workgroup; the launcher rounds it to 2, 4, 8 or 16
     int accumulate;
+    int mfma_batch;         // nonzero: windows of four activation columns go to the matrix-core kernel
     long long nnz;
     const void* qidx;       // nullptr -> no dense term
     const void* lut;

@@ -367,7 +367,7 @@ __device__ __forceinline__ void sparse_issue_gathers(const MatvecArgs& g, const 
         } else {
             const u32* src = reinterpret_cast<const u32*>(x + (size_t)q.c[k] * g.B);
 #pragma unroll
-            for (int h = 0; h < NB / 2; ++h) q.xw[k][h] = src[h];
+            for (int h = 0; h < NB / 2; ++h) q.xw[k][h] = src[2 * h < g.bn ? h : 0];   // a narrower window re-reads its first dword (never past the row)
         }
     }
 }
@@ -599,6 +599,211 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------- four activation columns on the matrix cores
+// With four activation columns the dense term is a small matrix product, and v_mfma_f32_4x4x4_16b_f16 fits it
+// exactly: the instruction multiplies, in each of its 16 blocks of four lanes, a 4 x 4 tile A (lane i supplies row i:
+// four consecutive k) by a 4 x 4 tile B (lane j supplies column j) and accumulates the 4 x 4 result (lane j keeps
+// column j).  Mapping:  lane l = 4 b + i of a dense wave owns the 32-column chunk b of the wave's slice and, for the
+// A operand, matrix row (4 rg + i) of the workgroup's row group rg; for the B operand it owns activation column i.
+//   * per row group and sub-slice a lane loads the 32 indices of ITS row (the wave reads four 192 / 256-byte row
+//     segments), turns them into 16 table offsets and 16 look-ups in ITS row's pair table -- the same decode as
+//     with one column -- and issues 8 MFMAs (four weights x four activations of all four columns each) instead of
+//     64 packed dot products;
+//   * the lane's 32 activations of column i come once per workgroup through a wave-private LDS transposition
+//     (coalesced loads of two x rows, pairs (x[2m][j], x[2m+1][j]) written to plane j, 64-byte reads back);
+//   * the accumulators (4 rows x column i) are summed over the 16 blocks with lane permutes at the very end.
+// A wave covers XS sub-slices of 512 columns (XS = 1, 2 or 4 by N), a workgroup G = 4 (or 2) row groups of 4 rows.
+// Windows of two columns use the same kernel with the other two columns zero.
+// The sparse wave and the final combination are those of the one-column kernel with NB = 4.
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kPlaneBytes = 1024 + 16;                    // 256 activation pairs of one column, plus a bank shift
+constexpr int kXPlanesBytes = 4 * kPlaneBytes;            // per dense wave
+
+template <int BITS, int G, int XS>
+__global__ void __launch_bounds__(1024) matvec_b4_kernel(MatvecArgs g) {
+    constexpr int NB = 4, R = 4 * G, K = 1 << BITS, UB = 8;
+    constexpr int TD = TableShape<BITS>::kTableDwords;
+    constexpr int kRawUnit = TableShape<BITS>::kRawUnit;
+    constexpr int kRawLanes = R * TableShape<BITS>::kRowBytes / kRawUnit;
+    constexpr int kSubCols = 512;                                    // columns of one sub-slice (16 chunks of 32)
+    __shared__ __align__(8) u32 tables[R * TD];
+    __shared__ __align__(16) uint16_t raw[R * K];
+    __shared__ float part[kMaxDenseWaves * R * NB];                  // [wave][row][column]
+    __shared__ float spart[(kMaxDenseWaves + 1) * R * NB];
+    extern __shared__ __align__(16) char xplanes[];                  // W * kXPlanesBytes
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int NW = blockDim.x >> 6;
+    const bool sparse = g.nnz > 0;
+    const int W = (g.N + kSubCols * XS - 1) / (kSubCols * XS);
+    const int r0 = blockIdx.x * R;
+    const int nrows = min(R, g.M - r0);
+    const int B = g.B, bn = g.bn;
+    const uint16_t* __restrict__ x = static_cast<const uint16_t*>(g.x) + g.bt0;
+
+    int rp[R + 1];
+    SparseRange sr;
+    load_row_pointers<NB, R>(g, r0, nrows, sparse, rp, sr);
+    float* myslots = spart + wave * R * NB;
+    if (lane < R * NB) myslots[lane] = 0.f;
+    int next_batch = 0;
+
+    if (wave < W) {
+        const int b = lane >> 2, i = lane & 3;
+        // ---- fp16 tables (wave 0), then activations, then the first index chunks
+        u32x4 rawv = {0, 0, 0, 0};
+        if (wave == 0 && lane < kRawLanes) {
+            const int u = lane * kRawUnit / TableShape<BITS>::kRowBytes;
+            const int row = min(r0 + u, g.M - 1);
+            const char* src = static_cast<const char*>(g.lut) + (size_t)row * TableShape<BITS>::kRowBytes + (lane * kRawUnit) % TableShape<BITS>::kRowBytes;
+            if constexpr (kRawUnit == 16) {
+                rawv = *reinterpret_cast<const u32x4*>(src);
+            } else {
+                const u32x2 v = *reinterpret_cast<const u32x2*>(src);
+                rawv.x = v.x; rawv.y = v.y;
+            }
+        }
+        // activations: xr[s][p] = (x[c + 2p][i], x[c + 2p + 1][i]) for the lane's chunk c = column of (sub-slice s, chunk b)
+        u32 xr[XS][16];
+        char* planes = xplanes + wave * kXPlanesBytes;
+#pragma unroll
+        for (int s = 0; s < XS; ++s) {
+            const int c0 = (wave * XS + s) * kSubCols;
+            u32 v0[4][2], v1[4][2];
+            const int off1 = bn > 2 ? 1 : 0;                         // a window of two columns is one dword per row: never read past it
+            if (B == 4) {
+                // rows of x are 8 bytes: a pair of rows is one aligned 16-byte load (N is even, so the pair is in range or not as a whole)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int ra = min(c0 + 2 * (t * 64 + lane), g.N - 2);
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(x + (size_t)ra * 4);
+                    v0[t][0] = v.x; v0[t][1] = v.y; v1[t][0] = v.z; v1[t][1] = v.w;
+                }
+            } else if (bn > 2 && (B & 3) == 0) {
+                // the window of a row is one aligned 8-byte load
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int ra = min(c0 + 2 * (t * 64 + lane), g.N - 2);
+                    const u32x2 a = *reinterpret_cast<const u32x2*>(x + (size_t)ra * B), bq = *reinterpret_cast<const u32x2*>(x + (size_t)(ra + 1) * B);
+                    v0[t][0] = a.x; v0[t][1] = a.y; v1[t][0] = bq.x; v1[t][1] = bq.y;
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int ra = min(c0 + 2 * (t * 64 + lane), g.N - 1), rb = min(c0 + 2 * (t * 64 + lane) + 1, g.N - 1);
+                    const u32* pa = reinterpret_cast<const u32*>(x + (size_t)ra * B);
+                    const u32* pb = reinterpret_cast<const u32*>(x + (size_t)rb * B);
+                    v0[t][0] = pa[0]; v1[t][0] = pb[0];
+                    v0[t][1] = pa[off1]; v1[t][1] = pb[off1];        // columns >= bn are zeroed below
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int m = t * 64 + lane;
+                *reinterpret_cast<u32*>(planes + 0 * kPlaneBytes + m * 4) = __builtin_amdgcn_perm(v1[t][0], v0[t][0], 0x05040100u);
+                *reinterpret_cast<u32*>(planes + 1 * kPlaneBytes + m * 4) = __builtin_amdgcn_perm(v1[t][0], v0[t][0], 0x07060302u);
+                *reinterpret_cast<u32*>(planes + 2 * kPlaneBytes + m * 4) = __builtin_amdgcn_perm(v1[t][1], v0[t][1], 0x05040100u);
+                *reinterpret_cast<u32*>(planes + 3 * kPlaneBytes + m * 4) = __builtin_amdgcn_perm(v1[t][1], v0[t][1], 0x07060302u);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const bool live = c0 + b * 32 < g.N && i < bn;
+            const u32x4* src = reinterpret_cast<const u32x4*>(planes + i * kPlaneBytes + b * 64);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const u32x4 v = src[k];
+                xr[s][4 * k + 0] = live ? v.x : 0u; xr[s][4 * k + 1] = live ? v.y : 0u; xr[s][4 * k + 2] = live ? v.z : 0u; xr[s][4 * k + 3] = live ? v.w : 0u;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        // index chunks: iteration it = rg * XS + s; the lane reads row (4 rg + i), chunk ((wave XS + s) 16 + b)
+        const size_t row_dwords = (size_t)g.N * BITS / 32;
+        const int last_chunk = g.N / 32 - 1;
+        constexpr int ITER = G * XS;
+        auto chunk_ptr = [&](int it) {
+            const int rg = it / XS, s = it % XS;
+            const int row = min(r0 + 4 * rg + i, g.M - 1);
+            const int cc = min((wave * XS + s) * 16 + b, last_chunk);
+            return static_cast<const u32*>(g.qidx) + (size_t)row * row_dwords + (size_t)cc * BITS;
+        };
+        LaneChunk<BITS> c[ITER];
+        constexpr int DP = ITER < 4 ? ITER : 4;                      // chunks requested ahead
+#pragma unroll
+        for (int it = 0; it < DP; ++it) c[it] = load_chunk<BITS>(chunk_ptr(it));
+        if (wave == 0) {
+            if (lane < kRawLanes) {
+                if constexpr (kRawUnit == 16) *reinterpret_cast<u32x4*>(raw + lane * 8) = rawv;
+                else *reinterpret_cast<u32x2*>(raw + lane * 4) = u32x2{rawv.x, rawv.y};
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            build_tables<BITS, R>(tables, raw, lane);
+        }
+        __syncthreads();
+        float4_t acc[G];
+#pragma unroll
+        for (int rg = 0; rg < G; ++rg) acc[rg] = float4_t{0.f, 0.f, 0.f, 0.f};
+        u32 w[2][16];
+        lookup_chunk<BITS>(c[0], tables + (0 * 4 + i) * TD, w[0]);
+        if constexpr (DP < ITER) c[DP] = load_chunk<BITS>(chunk_ptr(DP));
+#pragma unroll
+        for (int it = 0; it < ITER; ++it) {
+            if (it + 1 < ITER) {
+                lookup_chunk<BITS>(c[it + 1], tables + (((it + 1) / XS) * 4 + i) * TD, w[(it + 1) & 1]);
+                if (it + 1 + DP < ITER) c[it + 1 + DP] = load_chunk<BITS>(chunk_ptr(it + 1 + DP));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            const int rg = it / XS, s = it % XS;
+#pragma unroll
+            for (int m = 0; m < 8; ++m) {
+                const half4_t a = __builtin_bit_cast(half4_t, u32x2{w[it & 1][2 * m], w[it & 1][2 * m + 1]});
+                const half4_t bb = __builtin_bit_cast(half4_t, u32x2{xr[s][2 * m], xr[s][2 * m + 1]});
+                acc[rg] = __builtin_amdgcn_mfma_f32_4x4x4f16(a, bb, acc[rg], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // sum over the 16 blocks of the wave (lanes with the same column i), then lanes 0..3 hold the slice sums
+#pragma unroll
+        for (int rg = 0; rg < G; ++rg) {
+            float v[4] = {acc[rg].x, acc[rg].y, acc[rg].z, acc[rg].w};
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                v[r] += __shfl_xor(v[r], 4, 64); v[r] += __shfl_xor(v[r], 8, 64); v[r] += __shfl_xor(v[r], 16, 64); v[r] += __shfl_xor(v[r], 32, 64);
+                if (lane < 4) part[(wave * R + rg * 4 + r) * NB + lane] = v[r];
+            }
+        }
+        next_batch = UB;
+    } else {
+        __syncthreads();                                              // the dense waves' table barrier
+        if (sr.nbatch > 2) sparse_round<NB, R, UB>(g, x, sr, rp, 0, 1, lane, myslots);
+        else if (sr.nbatch > 0) sparse_round<NB, R, 2>(g, x, sr, rp, 0, 1, lane, myslots);
+        next_batch = UB;
+    }
+    for (int b0 = next_batch + wave; b0 < sr.nbatch; b0 += NW * UB)   // uniform
+        sparse_round<NB, R, UB>(g, x, sr, rp, b0, NW, lane, myslots);
+    __syncthreads();
+
+    uint16_t* __restrict__ y = static_cast<uint16_t*>(g.y) + g.bt0;
+    if (tid < nrows * NB) {
+        const int r = tid / NB, t = tid - r * NB;
+        if (t < bn) {
+            float sum = 0.f;
+            for (int wv = 0; wv < W; ++wv) sum += part[(wv * R + r) * NB + t];
+            if (sparse)
+                for (int wv = 0; wv < NW; ++wv) sum += spart[(wv * R + r) * NB + t];
+            const size_t o = (size_t)(r0 + r) * B + t;
+            if (g.accumulate) sum += half_bits_to_float(y[o]);
+            y[o] = float_to_half_bits(sum);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------- standard CSR kernel
 // one thread per row (the kernel the paper's App. C calls "standard")
 template <int NB>
@@ -752,6 +957,24 @@ static hipError_t launch_matvec_t(const MatvecArgs& g, hipStream_t s) {
     }
 }
 
+// windows of two or four activation columns with a dense term: the matrix-core kernel.  Sub-slices per wave by the
+// row length; 16 rows per workgroup (the activations a workgroup stages are then shared by twice as many rows:
+// 8192x8192 23.8 against 28.9 us) except for the widest rows, whose 4 sub-slices leave no registers for it.
+template <int BITS, int G, int XS>
+static hipError_t launch_matvec_b4_x(const MatvecArgs& g, hipStream_t s) {
+    const int W = (g.N + 512 * XS - 1) / (512 * XS);
+    const int waves = W + (g.nnz > 0 ? 1 : 0);
+    const int grid = (g.M + 4 * G - 1) / (4 * G);
+    hipLaunchKernelGGL((matvec_b4_kernel<BITS, G, XS>), dim3(grid), dim3(waves * kWave), (size_t)W * kXPlanesBytes, s, g);
+    return hipGetLastError();
+}
+template <int BITS>
+static hipError_t launch_matvec_b4(const MatvecArgs& g, hipStream_t s) {
+    if (g.N <= 512 * 14) return launch_matvec_b4_x<BITS, 4, 1>(g, s);
+    if (g.N <= 1024 * 14) return launch_matvec_b4_x<BITS, 4, 2>(g, s);
+    return launch_matvec_b4_x<BITS, 2, 4>(g, s);
+}
+
 template <int BITS>
 static hipError_t launch_matvec_b(const MatvecArgs& g0, hipStream_t s) {
     // Batch columns are processed in windows: 4 (or 2) columns per launch when the batch is even -- their
@@ -763,6 +986,7 @@ static hipError_t launch_matvec_b(const MatvecArgs& g0, hipStream_t s) {
         g.bt0 = t0; g.bn = min(step, g0.B - t0);
         hipError_t e;
         if (g.bn == 1) e = launch_matvec_t<BITS, 1>(g, s);
+        else if (g.qidx && g.mfma_batch) e = launch_matvec_b4<BITS>(g, s);       // windows of 2 or 4 columns
         else if (g.bn == 2) e = launch_matvec_t<BITS, 2>(g, s);
         else e = launch_matvec_t<BITS, 4>(g, s);
         if (e != hipSuccess) return e;
