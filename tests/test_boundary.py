@@ -106,3 +106,38 @@ def test_algorithmic_bytes_and_status_strings():
     assert L.sqllm_status_string(0) == b"SQLLM_OK" and L.sqllm_status_string(3) == b"SQLLM_ERR_SHAPE"
     old = sq.sqllm_set_rows_per_workgroup(8)
     assert sq.sqllm_set_rows_per_workgroup(old) == 8
+
+
+def test_quantize_argument_errors():
+    f = sq.sqllm_quantize_layer
+    ws = sq.sqllm_quantize_workspace_bytes(4, 128)
+    assert ws > 0 and ws % 4 == 0
+    ok = dict(M=4, N=128, bits=3, max_iter=8, w=A, sens=A, n_lo=1, n_hi=1, n_sens=1, workspace=A, workspace_bytes=ws,
+              qidx=A, lut=A, rowptr=A, cols=A, vals=A)
+
+    def call(status, **over):
+        a = dict(ok, **over)
+        expect(status, lambda stream: f(a["M"], a["N"], a["bits"], a["max_iter"], a["w"], a["sens"], a["n_lo"], a["n_hi"], a["n_sens"],
+                                        a["workspace"], a["workspace_bytes"], a["qidx"], a["lut"], a["rowptr"], a["cols"], a["vals"], None, stream))
+
+    call("SQLLM_ERR_BITS", bits=1)
+    call("SQLLM_ERR_BITS", bits=5)
+    call("SQLLM_ERR_SHAPE", N=100)
+    call("SQLLM_ERR_SHAPE", M=-1)
+    call("SQLLM_ERR_SHAPE", M=1 << 20, N=4096)                 # 2^32 weights: beyond the histogram counters
+    call("SQLLM_ERR_SHAPE", max_iter=-1)
+    call("SQLLM_ERR_SHAPE", workspace_bytes=ws - 4)
+    call("SQLLM_ERR_NNZ", n_lo=4 * 128)
+    call("SQLLM_ERR_NNZ", n_hi=-1)
+    call("SQLLM_ERR_NNZ", n_sens=4 * 128)
+    for name in ("w", "sens", "workspace", "qidx", "lut", "rowptr", "cols", "vals"):
+        call("SQLLM_ERR_NULL", **{name: None})
+    call("SQLLM_ERR_ALIGN", w=A + 8)
+    call("SQLLM_ERR_ALIGN", sens=A + 2)
+    call("SQLLM_ERR_ALIGN", lut=A + 4)
+    call("SQLLM_ERR_ALIGN", rowptr=A + 2)
+    call("SQLLM_ERR_ALIGN", vals=A + 1)
+    # nothing to extract: cols / vals may be NULL; M == 0: nothing is enqueued
+    f(0, 128, 3, 8, A, A, 0, 0, 0, A, ws, A, A, A, None, None, None, 0)
+    assert sq.extraction_counts(4096, 4096, 0.004, 0.0005) == (33554, 33554, 8388)
+    assert sq.extraction_counts(4096, 4096, 0.0, 0.0) == (0, 0, 0)
