@@ -614,7 +614,7 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
 //   * the accumulators (4 rows x column i) are summed over the 16 blocks with lane permutes at the very end.
 // A wave covers XS sub-slices of 512 columns (XS = 1, 2 or 4 by N), a workgroup G = 4 (or 2) row groups of 4 rows.
 // Windows of two columns use the same kernel with the other two columns zero.
-// The sparse wave and the final combination are those of the one-column kernel with NB = 4.
+// Two sparse waves (UB batches each) and the final combination work as in the one-column kernel, with NB = 4.
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 
@@ -628,10 +628,11 @@ __global__ void __launch_bounds__(1024) matvec_b4_kernel(MatvecArgs g) {
     constexpr int kRawUnit = TableShape<BITS>::kRawUnit;
     constexpr int kRawLanes = R * TableShape<BITS>::kRowBytes / kRawUnit;
     constexpr int kSubCols = 512;                                    // columns of one sub-slice (16 chunks of 32)
+    constexpr int kSparseWaves = 2;
     __shared__ __align__(8) u32 tables[R * TD];
     __shared__ __align__(16) uint16_t raw[R * K];
     __shared__ float part[kMaxDenseWaves * R * NB];                  // [wave][row][column]
-    __shared__ float spart[(kMaxDenseWaves + 1) * R * NB];
+    __shared__ float spart[(kMaxDenseWaves + 2) * R * NB];
     extern __shared__ __align__(16) char xplanes[];                  // W * kXPlanesBytes
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -778,12 +779,14 @@ __global__ void __launch_bounds__(1024) matvec_b4_kernel(MatvecArgs g) {
                 if (lane < 4) part[(wave * R + rg * 4 + r) * NB + lane] = v[r];
             }
         }
-        next_batch = UB;
+        next_batch = kSparseWaves * UB;
     } else {
         __syncthreads();                                              // the dense waves' table barrier
-        if (sr.nbatch > 2) sparse_round<NB, R, UB>(g, x, sr, rp, 0, 1, lane, myslots);
-        else if (sr.nbatch > 0) sparse_round<NB, R, 2>(g, x, sr, rp, 0, 1, lane, myslots);
-        next_batch = UB;
+        // two sparse waves, UB batches each: 16 rows carry about 10 batches at 0.45 %
+        const int b0 = (wave - W) * UB;
+        if (sr.nbatch > b0 + 2) sparse_round<NB, R, UB>(g, x, sr, rp, b0, 1, lane, myslots);
+        else if (sr.nbatch > b0) sparse_round<NB, R, 2>(g, x, sr, rp, b0, 1, lane, myslots);
+        next_batch = kSparseWaves * UB;
     }
     for (int b0 = next_batch + wave; b0 < sr.nbatch; b0 += NW * UB)   // uniform
         sparse_round<NB, R, UB>(g, x, sr, rp, b0, NW, lane, myslots);
@@ -963,7 +966,7 @@ static hipError_t launch_matvec_t(const MatvecArgs& g, hipStream_t s) {
 template <int BITS, int G, int XS>
 static hipError_t launch_matvec_b4_x(const MatvecArgs& g, hipStream_t s) {
     const int W = (g.N + 512 * XS - 1) / (512 * XS);
-    const int waves = W + (g.nnz > 0 ? 1 : 0);
+    const int waves = W + (g.nnz > 0 ? 2 : 0);
     const int grid = (g.M + 4 * G - 1) / (4 * G);
     hipLaunchKernelGGL((matvec_b4_kernel<BITS, G, XS>), dim3(grid), dim3(waves * kWave), (size_t)W * kXPlanesBytes, s, g);
     return hipGetLastError();
