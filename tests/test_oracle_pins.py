@@ -271,3 +271,35 @@ def test_tolerance_is_reachable_and_orders_the_accumulators():
     assert (e32 <= 2.0 ** -11 * np.abs(y[:, 0]) + L.N * 2.0 ** -24 * a[:, 0]).all()
     assert (e32 / (2e-3 * a[:, 0])).max() < 0.05
     assert e16.mean() > 5 * e32.mean()
+
+
+# ---------------------------------------------------------------- P2 again, with generated cases
+def test_pack_unpack_roundtrip_generated():
+    hyp = pytest.importorskip("hypothesis")
+    st = pytest.importorskip("hypothesis.strategies")
+
+    @hyp.settings(max_examples=60, deadline=None)
+    @hyp.given(bits=st.sampled_from([2, 3, 4]), groups=st.integers(1, 12), rows=st.integers(1, 3), seed=st.integers(0, 2 ** 31 - 1),
+               fill=st.sampled_from(["random", "zeros", "max", "alternate"]))
+    def check(bits, groups, rows, seed, fill):
+        N = 128 * groups
+        top = (1 << bits) - 1
+        if fill == "random":
+            idx = np.random.default_rng(seed).integers(0, top + 1, size=(rows, N), dtype=np.uint8)
+        elif fill == "zeros":
+            idx = np.zeros((rows, N), dtype=np.uint8)
+        elif fill == "max":
+            idx = np.full((rows, N), top, dtype=np.uint8)
+        else:
+            idx = (np.arange(rows * N, dtype=np.int64).reshape(rows, N) % 2 * top).astype(np.uint8)
+        q = gen.pack(idx, bits)
+        assert q.size == rows * N * bits // 8
+        assert np.array_equal(oracle.unpack(rows, N, bits, q), idx)
+        assert np.array_equal(nr.unpack(rows, N, bits, q), idx)
+        # a single set element changes exactly the bytes its bit field touches
+        j = seed % N
+        one = np.zeros((1, N), dtype=np.uint8); one[0, j] = top
+        touched = np.nonzero(gen.pack(one, bits))[0]
+        assert touched.min() == (j * bits) // 8 and touched.max() == (j * bits + bits - 1) // 8
+
+    check()
