@@ -12,7 +12,7 @@
  *               App. F quantises to 2 bits with the same format).
  *   S  (M x N)  sparse part in compressed-sparse-row form with fp16 values (Sec. 4.2: outliers and
  *               sensitive values kept in FP16 and stored in CSR).
- *   X  (N x B)  fp16 activations, B = 1..8 vectors;  Y (M x B) fp16.
+ *   X  (N x B)  fp16 activations, B = 1..16 vectors;  Y (M x B) fp16.
  *
  * STORAGE FORMAT (the paper does not fix one; this is the contract of this library)
  *   qidx   row i is a little-endian bit stream of N*b bits starting at byte i*N*b/8.  Element j owns stream
@@ -61,7 +61,7 @@ typedef enum {
     SQLLM_ERR_DEVICE = 8  /* the current device is not a gfx950 GPU                       */
 } sqllm_status;
 
-#define SQLLM_MAX_BATCH 8
+#define SQLLM_MAX_BATCH 16
 #define SQLLM_MAX_N 28672 /* widest row a workgroup covers with one 2048-column slice per wave (14 waves) */
 
 /* Dense term only (Sec. 4.3, the LUT-based matrix-vector kernel):

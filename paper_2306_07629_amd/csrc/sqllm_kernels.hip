@@ -821,6 +821,210 @@ __global__ void __launch_bounds__(1024) matvec_b4_kernel(MatvecArgs g) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------- up to sixteen activation columns on the matrix cores
+// y[M][B] = (D + S) x[N][B] for 1 <= B <= 16 as a product of 16 x 16 tiles (v_mfma_f32_16x16x16_f16).  The
+// instruction multiplies A (16 rows x 16 k) by B (16 k x 16 columns): lane l supplies A[l % 16][4 (l / 16) + e]
+// and B[4 (l / 16) + e][l % 16], e = 0..3, and keeps D[4 (l / 16) + e][l % 16].
+//   * A workgroup owns R = 16 RG rows and all N columns; its NW waves deal the 128-column windows of the row out
+//     among themselves (wave w takes windows w, w + NW, ...).  In a window, lane (r, q) = (l % 16, l / 16) loads
+//     the 32 indices of row r of each row group at columns 128 t + 32 q + [0, 32), looks them up in that row's
+//     pair table -- the same decode as with one column -- and feeds weights 4 m .. 4 m + 3 to MFMA m (m = 0..7);
+//     as B operand the same lane holds the activations of batch column r at the same 32 columns, gathered from x
+//     with 16-bit loads (any row stride B <= 16, any parity) once per window and used for all RG row groups.
+//   * The sparse term runs on the matrix cores as well: 16 consecutive nonzeros are one MFMA whose A operand
+//     holds value p in the row of nonzero p (a lane compares p against the two row pointers of ITS row) and
+//     whose B operand holds the activations of column cols[p].  The steps of a row group -- aligned groups of 16
+//     nonzeros overlapping its CSR range -- are dealt out to the waves like the windows, so a heavy row is
+//     spread over all waves and no reduction other than the accumulators is needed.
+//   * Accumulators of the waves are combined through LDS in a fixed order; y is rounded to fp16 once.
+typedef _Float16 half4v_t __attribute__((ext_vector_type(4)));
+typedef float float4v_t __attribute__((ext_vector_type(4)));
+
+template <int E>
+__device__ __forceinline__ u32 quad_bcast(u32 v) {
+    return (u32)__builtin_amdgcn_mov_dpp((int)v, E * 0x55, 0xF, 0xF, true);   // quad_perm: every lane reads lane E of its quad
+}
+
+constexpr int kB16SparseSteps = 4;                        // MFMA steps of the sparse term issued together
+
+template <int BITS, int RG>
+__global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
+    constexpr int R = 16 * RG, K = 1 << BITS;
+    constexpr int TD = TableShape<BITS>::kTableDwords;
+    constexpr int kRawUnit = TableShape<BITS>::kRawUnit;
+    constexpr int kRawLanes = R * TableShape<BITS>::kRowBytes / kRawUnit;
+    constexpr int kWinCols = 128;
+    extern __shared__ __align__(2048) char smem16[];
+    u32* tables = reinterpret_cast<u32*>(smem16);                                   // R tables, each 4 TD bytes (a power of two)
+    uint16_t* raw = reinterpret_cast<uint16_t*>(smem16 + R * TD * 4);               // fp16 tables as loaded
+    float* part = reinterpret_cast<float*>(smem16 + R * TD * 4 + R * K * 2);        // [wave][row][column]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int NW = blockDim.x >> 6;
+    const int r = lane & 15, q = lane >> 4;
+    const int r0 = blockIdx.x * R;
+    const int nrows = min(R, g.M - r0);
+    const int B = g.B;
+    const bool dense = g.qidx != nullptr, sparse = g.nnz > 0;
+    const uint16_t* __restrict__ x = static_cast<const uint16_t*>(g.x);
+    const int nwin = dense ? g.N / kWinCols : 0;
+
+    // ---- fp16 tables of the block's rows -> LDS
+    if (dense && tid < kRawLanes) {
+        const int u = tid * kRawUnit / TableShape<BITS>::kRowBytes;
+        const int row = min(r0 + u, g.M - 1);
+        const char* src = static_cast<const char*>(g.lut) + (size_t)row * TableShape<BITS>::kRowBytes + (tid * kRawUnit) % TableShape<BITS>::kRowBytes;
+        if constexpr (kRawUnit == 16) *reinterpret_cast<u32x4*>(raw + tid * 8) = *reinterpret_cast<const u32x4*>(src);
+        else *reinterpret_cast<u32x2*>(raw + tid * 4) = *reinterpret_cast<const u32x2*>(src);
+    }
+    // row pointers of the lane's own row in every row group (rows past M are empty)
+    int lo[RG], hi[RG];
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) {
+        lo[rg] = sparse ? g.rowptr[min(r0 + 16 * rg + r, g.M)] : 0;
+        hi[rg] = sparse ? g.rowptr[min(r0 + 16 * rg + r + 1, g.M)] : 0;
+    }
+    // ---- first window of this wave: indices and activations are requested before the tables are built
+    const size_t row_dwords = (size_t)g.N * BITS / 32;
+    const int nb = r < B ? r : 0;                                    // lanes of absent columns read column 0 and are zeroed
+    const u32 xmask = r < B ? 0xFFFFFFFFu : 0u;
+    auto load_idx = [&](int t, LaneChunk<BITS> (&c)[RG]) {
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg) {
+            const int row = min(r0 + 16 * rg + r, g.M - 1);
+            c[rg] = load_chunk<BITS>(static_cast<const u32*>(g.qidx) + (size_t)row * row_dwords + (size_t)(4 * t + q) * BITS);
+        }
+    };
+    auto load_xb = [&](int t, u32 (&xb)[16]) {
+        const uint16_t* src = x + (size_t)(kWinCols * t + 32 * q) * B + nb;
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const u32 a = src[(size_t)(2 * p) * B], b = src[(size_t)(2 * p + 1) * B];
+            xb[p] = (a | (b << 16)) & xmask;
+        }
+    };
+    LaneChunk<BITS> c[RG], cn[RG];
+    u32 xb[16], xn[16];
+    int t = wave;
+    if (t < nwin) { load_idx(t, c); load_xb(t, xb); }
+    __syncthreads();
+    if (dense)
+        for (int u = wave; u < R; u += NW) build_tables<BITS, 1>(tables + u * TD, raw + u * K, lane);
+    __syncthreads();
+
+    float4v_t acc[RG];
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) acc[rg] = float4v_t{0.f, 0.f, 0.f, 0.f};
+
+    // ---- dense term: windows t, t + NW, ...; the next window is requested before the current one is decoded
+    for (; t < nwin; t += NW) {
+        const int tn = t + NW < nwin ? t + NW : t;                   // the last window is requested twice rather than branching around loads
+        load_idx(tn, cn);
+        load_xb(tn, xn);
+        u32 w[2][16];
+        lookup_chunk<BITS>(c[0], tables + r * TD, w[0]);
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg) {
+            if (rg + 1 < RG) lookup_chunk<BITS>(c[rg + 1], tables + (16 * (rg + 1) + r) * TD, w[(rg + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int m = 0; m < 8; ++m) {
+                const half4v_t a = __builtin_bit_cast(half4v_t, u32x2{w[rg & 1][2 * m], w[rg & 1][2 * m + 1]});
+                const half4v_t b = __builtin_bit_cast(half4v_t, u32x2{xb[2 * m], xb[2 * m + 1]});
+                acc[rg] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, acc[rg], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg) c[rg] = cn[rg];
+#pragma unroll
+        for (int p = 0; p < 16; ++p) xb[p] = xn[p];
+    }
+
+    // ---- sparse term: step j covers nonzeros [16 j, 16 j + 16); flat step f of the block = (row group, j)
+    if (sparse) {
+        int first[RG], count[RG], total = 0;                         // uniform
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg) {
+            const int P0 = __builtin_amdgcn_readlane(lo[rg], 0), P1 = __builtin_amdgcn_readlane(hi[rg], 15);
+            first[rg] = P0 >> 4;
+            count[rg] = P1 > P0 ? ((P1 - 1) >> 4) - (P0 >> 4) + 1 : 0;
+            total += count[rg];
+        }
+        const int last_nz = (int)g.nnz - 1;
+        const uint16_t* __restrict__ vals = static_cast<const uint16_t*>(g.vals);
+        for (int f0 = wave; f0 < total; f0 += NW * kB16SparseSteps) {
+            int srg[kB16SparseSteps], sj[kB16SparseSteps];           // uniform: row group and step of each slot (-1: none)
+            u32 col[kB16SparseSteps], val[kB16SparseSteps];
+#pragma unroll
+            for (int k = 0; k < kB16SparseSteps; ++k) {
+                int f = f0 + k * NW;
+                srg[k] = -1; sj[k] = 0;
+                if (f < total) {
+#pragma unroll
+                    for (int rg = 0; rg < RG; ++rg) {
+                        if (srg[k] < 0) {
+                            if (f < count[rg]) { srg[k] = rg; sj[k] = first[rg] + f; }
+                            else f -= count[rg];
+                        }
+                    }
+                }
+                const int pl = min(16 * sj[k] + 4 * q + (lane & 3), last_nz);   // lane e of a quad fetches nonzero 16 j + 4 q + e
+                col[k] = (u32)g.cols[pl];
+                val[k] = vals[pl];
+            }
+            u32 xa[kB16SparseSteps][2], aa[kB16SparseSteps][2];
+#pragma unroll
+            for (int k = 0; k < kB16SparseSteps; ++k) {
+                const u32 c0 = quad_bcast<0>(col[k]), c1 = quad_bcast<1>(col[k]), c2 = quad_bcast<2>(col[k]), c3 = quad_bcast<3>(col[k]);
+                const u32 x0 = x[(size_t)c0 * B + nb], x1 = x[(size_t)c1 * B + nb], x2 = x[(size_t)c2 * B + nb], x3 = x[(size_t)c3 * B + nb];
+                xa[k][0] = (x0 | (x1 << 16)) & xmask;
+                xa[k][1] = (x2 | (x3 << 16)) & xmask;
+            }
+#pragma unroll
+            for (int k = 0; k < kB16SparseSteps; ++k) {
+                const int p0 = 16 * sj[k] + 4 * q;
+                int l = 0, h = 0;
+#pragma unroll
+                for (int rg = 0; rg < RG; ++rg) { if (srg[k] == rg) { l = lo[rg]; h = hi[rg]; } }
+                const u32 v0 = quad_bcast<0>(val[k]), v1 = quad_bcast<1>(val[k]), v2 = quad_bcast<2>(val[k]), v3 = quad_bcast<3>(val[k]);
+                const u32 a0 = (p0 + 0 >= l && p0 + 0 < h) ? v0 : 0u, a1 = (p0 + 1 >= l && p0 + 1 < h) ? v1 : 0u;
+                const u32 a2 = (p0 + 2 >= l && p0 + 2 < h) ? v2 : 0u, a3 = (p0 + 3 >= l && p0 + 3 < h) ? v3 : 0u;
+                aa[k][0] = a0 | (a1 << 16);
+                aa[k][1] = a2 | (a3 << 16);
+            }
+#pragma unroll
+            for (int k = 0; k < kB16SparseSteps; ++k) {
+                const half4v_t a = __builtin_bit_cast(half4v_t, u32x2{aa[k][0], aa[k][1]});
+                const half4v_t b = __builtin_bit_cast(half4v_t, u32x2{xa[k][0], xa[k][1]});
+#pragma unroll
+                for (int rg = 0; rg < RG; ++rg)
+                    if (srg[k] == rg) acc[rg] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, acc[rg], 0, 0, 0);   // uniform branch
+            }
+        }
+    }
+
+    // ---- combine the waves' accumulators in a fixed order: lane (r, q) holds rows 4 q + e of column r
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) {
+        const float v[4] = {acc[rg].x, acc[rg].y, acc[rg].z, acc[rg].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) part[(wave * R + 16 * rg + 4 * q + e) * 16 + r] = v[e];
+    }
+    __syncthreads();
+    uint16_t* __restrict__ y = static_cast<uint16_t*>(g.y);
+    for (int o = tid; o < R * 16; o += blockDim.x) {
+        const int row = o >> 4, n = o & 15;
+        if (row < nrows && n < B) {
+            float sum = 0.f;
+            for (int wv = 0; wv < NW; ++wv) sum += part[(wv * R + row) * 16 + n];
+            const size_t yo = (size_t)(r0 + row) * B + n;
+            if (g.accumulate) sum += half_bits_to_float(y[yo]);
+            y[yo] = float_to_half_bits(sum);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------- standard CSR kernel
 // one thread per row (the kernel the paper's App. C calls "standard")
 template <int NB>
@@ -992,8 +1196,43 @@ static hipError_t launch_matvec_b4(const MatvecArgs& g, hipStream_t s) {
     return launch_matvec_b4_x<BITS, 2, 4>(g, s);
 }
 
+// up to 16 columns in one launch: 32 rows per workgroup when that still gives every compute unit a workgroup
+#ifndef SQ_B16_NW
+#define SQ_B16_NW 16
+#endif
+#ifndef SQ_B16_RG2_MIN_M
+#define SQ_B16_RG2_MIN_M 8192
+#endif
+template <int BITS, int RG>
+static hipError_t launch_matvec_b16_r(const MatvecArgs& g, hipStream_t s) {
+    constexpr int R = 16 * RG;
+    const int nwin = g.qidx ? g.N / 128 : 0;
+    const int NW = nwin ? (nwin < SQ_B16_NW ? nwin : SQ_B16_NW) : 4;
+    const size_t lds = (size_t)R * TableShape<BITS>::kTableDwords * 4 + (size_t)R * (2 << BITS) + (size_t)NW * R * 64;
+    static bool raised = false;                                      // idempotent: a race only repeats the call
+    if (!raised) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&matvec_b16_kernel<BITS, RG>), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    hipLaunchKernelGGL((matvec_b16_kernel<BITS, RG>), dim3((g.M + R - 1) / R), dim3(NW * kWave), lds, s, g);
+    return hipGetLastError();
+}
+template <int BITS>
+static hipError_t launch_matvec_b16(const MatvecArgs& g, hipStream_t s) {
+    return g.M >= SQ_B16_RG2_MIN_M ? launch_matvec_b16_r<BITS, 2>(g, s) : launch_matvec_b16_r<BITS, 1>(g, s);
+}
+
+#ifndef SQ_B16_MIN_B
+#define SQ_B16_MIN_B 5
+#endif
 template <int BITS>
 static hipError_t launch_matvec_b(const MatvecArgs& g0, hipStream_t s) {
+    if (g0.qidx && g0.mfma_batch && (g0.B >= SQ_B16_MIN_B || g0.B == 3)) {
+        MatvecArgs g = g0;
+        g.bt0 = 0; g.bn = g0.B;
+        return launch_matvec_b16<BITS>(g, s);
+    }
     // Batch columns are processed in windows: 4 (or 2) columns per launch when the batch is even -- their
     // activations must fit in registers -- and one column per launch when it is odd (rows of x are then not
     // dword aligned).  B = 1, 2 and 4 are single launches.
@@ -1016,14 +1255,18 @@ hipError_t launch_matvec(const MatvecArgs& g, hipStream_t s) {
 }
 
 hipError_t launch_csr_rowwise(const MatvecArgs& g0, hipStream_t s) {
-    MatvecArgs g = g0;
-    g.bt0 = 0; g.bn = g.B;
-    const int grid = (g.M + 255) / 256;
-    if (g.B == 1) hipLaunchKernelGGL((csr_rowwise_kernel<1>), dim3(grid), dim3(256), 0, s, g);
-    else if (g.B == 2) hipLaunchKernelGGL((csr_rowwise_kernel<2>), dim3(grid), dim3(256), 0, s, g);
-    else if (g.B <= 4) hipLaunchKernelGGL((csr_rowwise_kernel<4>), dim3(grid), dim3(256), 0, s, g);
-    else hipLaunchKernelGGL((csr_rowwise_kernel<8>), dim3(grid), dim3(256), 0, s, g);
-    return hipGetLastError();
+    const int grid = (g0.M + 255) / 256;
+    for (int t0 = 0; t0 < g0.B; t0 += 8) {                           // windows of at most eight columns
+        MatvecArgs g = g0;
+        g.bt0 = t0; g.bn = min(8, g0.B - t0);
+        if (g.bn == 1) hipLaunchKernelGGL((csr_rowwise_kernel<1>), dim3(grid), dim3(256), 0, s, g);
+        else if (g.bn == 2) hipLaunchKernelGGL((csr_rowwise_kernel<2>), dim3(grid), dim3(256), 0, s, g);
+        else if (g.bn <= 4) hipLaunchKernelGGL((csr_rowwise_kernel<4>), dim3(grid), dim3(256), 0, s, g);
+        else hipLaunchKernelGGL((csr_rowwise_kernel<8>), dim3(grid), dim3(256), 0, s, g);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_decode(int M, int N, int bits, const void* qidx, const void* lut, void* idx_out, void* w_out, hipStream_t s) {
@@ -1051,7 +1294,8 @@ hipError_t launch_fp16_gemv(int M, int N, int B, const void* w, const void* x, v
     if (B == 1) hipLaunchKernelGGL((fp16_gemv_kernel<1, RB>), dim3(grid), dim3(WAVES * kWave), 0, s, M, N, B, w, x, y);
     else if (B == 2) hipLaunchKernelGGL((fp16_gemv_kernel<2, RB>), dim3(grid), dim3(WAVES * kWave), 0, s, M, N, B, w, x, y);
     else if (B <= 4) hipLaunchKernelGGL((fp16_gemv_kernel<4, RB>), dim3(grid), dim3(WAVES * kWave), 0, s, M, N, B, w, x, y);
-    else hipLaunchKernelGGL((fp16_gemv_kernel<8, RB>), dim3(grid), dim3(WAVES * kWave), 0, s, M, N, B, w, x, y);
+    else if (B <= 8) hipLaunchKernelGGL((fp16_gemv_kernel<8, RB>), dim3(grid), dim3(WAVES * kWave), 0, s, M, N, B, w, x, y);
+    else hipLaunchKernelGGL((fp16_gemv_kernel<16, RB>), dim3(grid), dim3(WAVES * kWave), 0, s, M, N, B, w, x, y);
     return hipGetLastError();
 }
 

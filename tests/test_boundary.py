@@ -49,7 +49,7 @@ def test_lut_gemv_argument_errors():
     expect("SQLLM_ERR_SHAPE", f, 4, 64, 4, 1, A, A, A, A)
     expect("SQLLM_ERR_SHAPE", f, 4, 28672 + 128, 3, 1, A, A, A, A)
     expect("SQLLM_ERR_BATCH", f, 4, 128, 3, 0, A, A, A, A)
-    expect("SQLLM_ERR_BATCH", f, 4, 128, 3, 9, A, A, A, A)
+    expect("SQLLM_ERR_BATCH", f, 4, 128, 3, 17, A, A, A, A)
     expect("SQLLM_ERR_NULL", f, 4, 128, 3, 1, None, A, A, A)
     expect("SQLLM_ERR_NULL", f, 4, 128, 3, 1, A, None, A, A)
     expect("SQLLM_ERR_NULL", f, 4, 128, 3, 1, A, A, None, A)
