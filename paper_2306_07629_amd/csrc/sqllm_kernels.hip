@@ -845,9 +845,128 @@ __device__ __forceinline__ u32 quad_bcast(u32 v) {
     return (u32)__builtin_amdgcn_mov_dpp((int)v, E * 0x55, 0xF, 0xF, true);   // quad_perm: every lane reads lane E of its quad
 }
 
-constexpr int kB16SparseSteps = 4;                        // MFMA steps of the sparse term issued together
+constexpr int kB16StageBytes = 16 * (256 + 16);           // one window of x for 16 columns: 16 planes of 64 row pairs (fast path), or the window as it lies in memory plus the shifts of its quarters (4224 bytes)
 
-template <int BITS, int RG>
+// Entry-major tables.  Lane l of a 16-lane group decodes its OWN matrix row, so the 32 lanes the LDS serves together
+// read 32 different (row, entry) addresses; with one table after the other every row's entries overlay the same
+// banks and the look-up takes ~7.5 cycles (hardware counters: 58 % of the LDS cycles were bank conflicts).  Here entry
+// e of the block's row rho lives at byte (e R + rho) * kEntryBytes: a row owns one bank (two for b = 2), rows never
+// collide with each other and only the two lanes of one row can (2 passes per 32 lanes, as with one shared table).
+// LDS addresses of the 16 (b = 2: 8) entries of a lane's chunk: entry index times the entry stride 1 << S, OR the
+// row's offset `base` < 1 << S (the tables start at LDS address 0: the kernel has no other static or dynamic LDS before them):
+template <int S>
+__device__ __forceinline__ void entry_offsets(const LaneChunk<3>& c, u32 base, u32 (&a)[16]) {
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+        const int bit = 6 * p, d = bit >> 5, pos = bit & 31;
+        const u32 f = pos + 6 <= 32 ? (c.q[d] >> pos) & 63u : funnel_shr(c.q[(d + 1) % 3], c.q[d], pos) & 63u;   // a pair never starts in the last 6 bits of dword 2
+        a[p] = (f << S) | base;
+    }
+}
+template <int S>
+__device__ __forceinline__ void entry_offsets(const LaneChunk<4>& c, u32 base, u32 (&a)[16]) {
+#pragma unroll
+    for (int p = 0; p < 16; ++p) a[p] = (((c.q[p >> 2] >> (8 * (p & 3))) & 0xFFu) << S) | base;
+}
+template <int S>
+__device__ __forceinline__ void entry_offsets(const LaneChunk<2>& c, u32 base, u32 (&a)[16]) {
+#pragma unroll
+    for (int p = 0; p < 8; ++p) a[p] = (((c.q[p >> 2] >> (8 * (p & 3))) & 0xFFu) << S) | base;
+#pragma unroll
+    for (int p = 8; p < 16; ++p) a[p] = 0;
+}
+template <int BITS, int S>
+__device__ __forceinline__ void lookup_chunk_at(const LaneChunk<BITS>& c, u32 base, u32 (&w)[16]) {
+    u32 a[16];
+    entry_offsets<S>(c, base, a);
+    if constexpr (BITS == 2) {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const u32x2 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x2*>(a[p]);
+            w[2 * p] = v.x; w[2 * p + 1] = v.y;
+        }
+    } else {
+#pragma unroll
+        for (int p = 0; p < 16; ++p) w[p] = *reinterpret_cast<const __attribute__((address_space(3))) u32*>(a[p]);
+    }
+}
+
+// Sparse term of the 16-column kernel.  Step j covers the nonzeros [16 j, 16 j + 16); the steps overlapping the CSR
+// range of row group rg are first[rg] .. first[rg] + count[rg] - 1, and flat step f of the block runs through the
+// row groups in order.  A wave handles NS flat steps f0, f0 + NW, ... per round: all column / value loads, then all
+// activation gathers, then the products.  Slots past the block's last step re-read step 0 and contribute nothing.
+template <int RG, int NS>
+struct B16SparseSlots {
+    int srg[NS], sj[NS];      // uniform: row group (-1: none) and step of each slot
+    u32 col[NS], val[NS];     // lane e of a quad holds nonzero 16 j + 4 q + e
+};
+
+template <int RG, int NS>
+__device__ __forceinline__ void b16_sparse_issue(const MatvecArgs& g, const int (&first)[RG], const int (&count)[RG], int total, int f0, int NW,
+                                                 int lane, B16SparseSlots<RG, NS>& S) {
+    const int last_nz = (int)g.nnz - 1;
+    const uint16_t* __restrict__ vals = static_cast<const uint16_t*>(g.vals);
+    const int e4 = 4 * (lane >> 4) + (lane & 3);
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        int f = f0 + k * NW;
+        S.srg[k] = -1; S.sj[k] = 0;
+        if (f < total) {
+#pragma unroll
+            for (int rg = 0; rg < RG; ++rg) {
+                if (S.srg[k] < 0) {
+                    if (f < count[rg]) { S.srg[k] = rg; S.sj[k] = first[rg] + f; }
+                    else f -= count[rg];
+                }
+            }
+        }
+        const int pl = min(16 * S.sj[k] + e4, last_nz);
+        S.col[k] = (u32)g.cols[pl];
+        S.val[k] = vals[pl];
+    }
+}
+
+template <int RG, int NS>
+__device__ __forceinline__ void b16_sparse_finish(const uint16_t* __restrict__ x, int B, int nb, u32 xmask, int lane, const int (&lo)[RG], const int (&hi)[RG],
+                                                  const B16SparseSlots<RG, NS>& S, float4v_t (&acc)[RG]) {
+    const int q = lane >> 4;
+    const char* xb = reinterpret_cast<const char*>(x);
+    u32 xa[NS][2], aa[NS][2];
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        // byte offsets fit 32 bits: N * B * 2 < 2^20
+        const u32 c0 = quad_bcast<0>(S.col[k]), c1 = quad_bcast<1>(S.col[k]), c2 = quad_bcast<2>(S.col[k]), c3 = quad_bcast<3>(S.col[k]);
+        const u32 x0 = *reinterpret_cast<const uint16_t*>(xb + 2u * (c0 * (u32)B + (u32)nb)), x1 = *reinterpret_cast<const uint16_t*>(xb + 2u * (c1 * (u32)B + (u32)nb));
+        const u32 x2 = *reinterpret_cast<const uint16_t*>(xb + 2u * (c2 * (u32)B + (u32)nb)), x3 = *reinterpret_cast<const uint16_t*>(xb + 2u * (c3 * (u32)B + (u32)nb));
+        xa[k][0] = (x0 | (x1 << 16)) & xmask;
+        xa[k][1] = (x2 | (x3 << 16)) & xmask;
+    }
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        const int p0 = 16 * S.sj[k] + 4 * q;
+        int l = 0, h = 0;
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg) { if (S.srg[k] == rg) { l = lo[rg]; h = hi[rg]; } }
+        const u32 v0 = quad_bcast<0>(S.val[k]), v1 = quad_bcast<1>(S.val[k]), v2 = quad_bcast<2>(S.val[k]), v3 = quad_bcast<3>(S.val[k]);
+        // value p goes to the row whose CSR range holds p: 0 <= p - l < h - l as one unsigned comparison
+        const u32 span = (u32)(h - l), d0 = (u32)(p0 - l);
+        const u32 a0 = d0 < span ? v0 : 0u, a1 = d0 + 1u < span ? v1 : 0u, a2 = d0 + 2u < span ? v2 : 0u, a3 = d0 + 3u < span ? v3 : 0u;
+        aa[k][0] = a0 | (a1 << 16);
+        aa[k][1] = a2 | (a3 << 16);
+    }
+#pragma unroll
+    for (int k = 0; k < NS; ++k) {
+        const half4v_t a = __builtin_bit_cast(half4v_t, u32x2{aa[k][0], aa[k][1]});
+        const half4v_t b = __builtin_bit_cast(half4v_t, u32x2{xa[k][0], xa[k][1]});
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg)
+            if (S.srg[k] == rg) acc[rg] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, acc[rg], 0, 0, 0);   // uniform branch
+    }
+}
+
+// B4 > 0: the batch is exactly 4 B4 columns (4, 8, 12 or 16) and the activations take the fast path below;
+// B4 == 0: any batch up to 16, activations staged as they lie in memory.
+template <int BITS, int RG, int B4>
 __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
     constexpr int R = 16 * RG, K = 1 << BITS;
     constexpr int TD = TableShape<BITS>::kTableDwords;
@@ -857,9 +976,10 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
     extern __shared__ __align__(2048) char smem16[];
     u32* tables = reinterpret_cast<u32*>(smem16);                                   // R tables, each 4 TD bytes (a power of two)
     uint16_t* raw = reinterpret_cast<uint16_t*>(smem16 + R * TD * 4);               // fp16 tables as loaded
-    float* part = reinterpret_cast<float*>(smem16 + R * TD * 4 + R * K * 2);        // [wave][row][column]
+    char* stage0 = smem16 + R * TD * 4 + R * K * 2;                                 // per wave: staging of one x window, later its partial sums
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // uniform, and known to be: addresses derived from it stay in scalar registers
     const int NW = blockDim.x >> 6;
     const int r = lane & 15, q = lane >> 4;
     const int r0 = blockIdx.x * R;
@@ -868,6 +988,9 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
     const bool dense = g.qidx != nullptr, sparse = g.nnz > 0;
     const uint16_t* __restrict__ x = static_cast<const uint16_t*>(g.x);
     const int nwin = dense ? g.N / kWinCols : 0;
+    char* stage = stage0 + wave * kB16StageBytes;
+    const int NWD = dense ? NW : 0;                                  // every wave takes windows of the dense term (if there is one) ...
+    const bool sparse_wave = sparse;                                 // ... and afterwards a share of the sparse term
 
     // ---- fp16 tables of the block's rows -> LDS
     if (dense && tid < kRawLanes) {
@@ -881,10 +1004,9 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
     int lo[RG], hi[RG];
 #pragma unroll
     for (int rg = 0; rg < RG; ++rg) {
-        lo[rg] = sparse ? g.rowptr[min(r0 + 16 * rg + r, g.M)] : 0;
-        hi[rg] = sparse ? g.rowptr[min(r0 + 16 * rg + r + 1, g.M)] : 0;
+        lo[rg] = sparse_wave ? g.rowptr[min(r0 + 16 * rg + r, g.M)] : 0;
+        hi[rg] = sparse_wave ? g.rowptr[min(r0 + 16 * rg + r + 1, g.M)] : 0;
     }
-    // ---- first window of this wave: indices and activations are requested before the tables are built
     const size_t row_dwords = (size_t)g.N * BITS / 32;
     const int nb = r < B ? r : 0;                                    // lanes of absent columns read column 0 and are zeroed
     const u32 xmask = r < B ? 0xFFFFFFFFu : 0u;
@@ -895,37 +1017,162 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
             c[rg] = load_chunk<BITS>(static_cast<const u32*>(g.qidx) + (size_t)row * row_dwords + (size_t)(4 * t + q) * BITS);
         }
     };
-    auto load_xb = [&](int t, u32 (&xb)[16]) {
-        const uint16_t* src = x + (size_t)(kWinCols * t + 32 * q) * B + nb;
+    // Activations of a window: the 128 rows of x are 64 B contiguous dwords.  They are copied to LDS as they lie in
+    // memory (coalesced loads, 16 B dwords per quarter of the window, every quarter shifted by 32 bytes so that the four
+    // lane groups read different banks), and each lane then picks the 32 halves of ITS column with 16-bit reads.
+    // Load slot (qq, ii) covers dwords 64 ii + lane of quarter qq; slots past the quarter re-read its last dword.
+    const int qd = 16 * B;                                           // dwords of one quarter (32 rows of x)
+    u32 eoff[4];                                                     // byte offset of the lane's dword in load slot ii of a quarter
 #pragma unroll
-        for (int p = 0; p < 16; ++p) {
-            const u32 a = src[(size_t)(2 * p) * B], b = src[(size_t)(2 * p + 1) * B];
-            xb[p] = (a | (b << 16)) & xmask;
+    for (int ii = 0; ii < 4; ++ii) eoff[ii] = 4u * (u32)min(64 * ii + lane, qd - 1);
+    const u32 stage_lds = (u32)(size_t)stage;                        // LDS byte address of the wave's staging area (uniform)
+    constexpr int kEntryBytes = 4 * TableShape<BITS>::kEntryDwords;   // 4, or 8 for b = 2
+    constexpr int kStrideLog2 = (RG == 2 ? 5 : 4) + (kEntryBytes == 8 ? 3 : 2);   // log2(R * kEntryBytes): bytes from one entry to the next
+    const u32 tab0 = (u32)r * kEntryBytes;                           // the lane's row of row group 0; the tables start at LDS address 0
+    constexpr int BT = 4 * B4, kPitch = 256 + 16;                    // fast path: columns, bytes of one column's 64 row pairs (+ bank shift)
+    auto load_xblock = [&](int t, u32 (&v)[16]) {
+        if constexpr (B4 == 4 || B4 == 2) {
+            // fully coalesced: load i of lane l is the 16-byte unit 64 i + l of the window (half a row of 16 columns, or
+            // a whole row of 8); the neighbouring row sits two lanes (one lane) further and is fetched with a quad permute
+            const u32x4* src = reinterpret_cast<const u32x4*>(x + (size_t)t * kWinCols * BT) + lane;
+#pragma unroll
+            for (int i = 0; i < B4; ++i) {
+                const u32x4 v4 = src[64 * i];
+                v[4 * i] = v4.x; v[4 * i + 1] = v4.y; v[4 * i + 2] = v4.z; v[4 * i + 3] = v4.w;
+            }
+        } else if constexpr (B4 > 0) {
+            // lane l fetches rows 2 l and 2 l + 1 of the window: 4 BT contiguous bytes
+            const u32x4* src = reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(x + (size_t)t * kWinCols * BT) + (u32)lane * 4u * BT);
+#pragma unroll
+            for (int i = 0; i < B4; ++i) {
+                const u32x4 v4 = src[i];
+                v[4 * i] = v4.x; v[4 * i + 1] = v4.y; v[4 * i + 2] = v4.z; v[4 * i + 3] = v4.w;
+            }
+        } else {
+            const char* src = reinterpret_cast<const char*>(x + (size_t)t * kWinCols * B);   // uniform
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+                const char* sq = src + (size_t)(4 * qq * qd);        // uniform
+#pragma unroll
+                for (int ii = 0; ii < 4; ++ii) v[4 * qq + ii] = *reinterpret_cast<const u32*>(sq + eoff[ii]);
+            }
         }
     };
-    LaneChunk<BITS> c[RG], cn[RG];
-    u32 xb[16], xn[16];
-    int t = wave;
-    if (t < nwin) { load_idx(t, c); load_xb(t, xb); }
+    const u32 rd0 = stage_lds + 4u * q * qd + 32u * q + 2u * nb;     // slow path: row 32 q of the window, column nb
+    auto stage_x = [&](const u32 (&v)[16], u32 (&xb)[16]) {
+        if constexpr (B4 == 4 || B4 == 2) {
+            // own row k and its neighbour k ^ 1 (lane ^ 2 for 16 columns, lane ^ 1 for 8): the lane of the even row forms
+            // the pair (x[k][n], x[k + 1][n]) of the even column n of each dword, the lane of the odd row that of the odd column
+            const bool keven = B4 == 4 ? (lane & 2) == 0 : (lane & 1) == 0;
+            const u32 sel = keven ? 0x05040100u : 0x03020706u;
+            const u32 wr = stage_lds + (B4 == 4 ? (u32)(8 * (lane & 1) + (keven ? 0 : 1)) * kPitch + (u32)(lane >> 2) * 4u
+                                                : (u32)(keven ? 0 : 1) * kPitch + (u32)(lane >> 1) * 4u);
+#pragma unroll
+            for (int i = 0; i < B4; ++i)
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const u32 own = v[4 * i + d];
+                    const u32 other = (u32)__builtin_amdgcn_mov_dpp((int)own, B4 == 4 ? 0x4E : 0xB1, 0xF, 0xF, true);   // quad_perm [2,3,0,1] / [1,0,3,2]
+                    const u32 pair = __builtin_amdgcn_perm(other, own, sel);
+                    *reinterpret_cast<__attribute__((address_space(3))) u32*>(wr + (u32)(2 * d) * kPitch + (B4 == 4 ? 64u : 128u) * i) = pair;
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const u32 rd = stage_lds + (u32)nb * kPitch + (u32)q * 64u;
+            const u32 xm = B4 == 4 ? 0xFFFFFFFFu : xmask;            // with 16 columns every lane's column exists
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const u32x4 v4 = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(rd + 16u * i);
+                xb[4 * i] = v4.x & xm; xb[4 * i + 1] = v4.y & xm; xb[4 * i + 2] = v4.z & xm; xb[4 * i + 3] = v4.w & xm;
+            }
+        } else if constexpr (B4 > 0) {
+            // v[d], d < BT / 2: columns 2 d, 2 d + 1 of row 2 l; v[BT / 2 + d]: the same of row 2 l + 1.  The pair
+            // (x[2 l][n], x[2 l + 1][n]) goes to dword l of column n's plane; lane (n, q) then reads 64 bytes of plane n.
+#pragma unroll
+            for (int n = 0; n < BT; ++n) {
+                const u32 pair = __builtin_amdgcn_perm(v[BT / 2 + n / 2], v[n / 2], (n & 1) ? 0x07060302u : 0x05040100u);
+                *reinterpret_cast<__attribute__((address_space(3))) u32*>(stage_lds + (u32)n * kPitch + (u32)lane * 4u) = pair;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const u32 rd = stage_lds + (u32)nb * kPitch + (u32)q * 64u;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const u32x4 v4 = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(rd + 16u * i);
+                xb[4 * i] = v4.x & xmask; xb[4 * i + 1] = v4.y & xmask; xb[4 * i + 2] = v4.z & xmask; xb[4 * i + 3] = v4.w & xmask;
+            }
+        } else {
+            // the strides are recomputed from a copy of B the compiler cannot see through: hoisted out of the window
+            // loop the 48 addresses would occupy 48 registers for the whole kernel
+            u32 Bl = (u32)B;
+            asm volatile("" : "+s"(Bl));
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+                const u32 base = stage_lds + 64u * qq * Bl + 32u * qq;   // uniform
+#pragma unroll
+                for (int ii = 0; ii < 4; ++ii)
+                    *reinterpret_cast<__attribute__((address_space(3))) u32*>(base + eoff[ii]) = v[4 * qq + ii];
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int p = 0; p < 16; ++p) {
+                const u32 a = *reinterpret_cast<const __attribute__((address_space(3))) uint16_t*>(rd0 + (u32)(2 * p) * 2u * Bl);
+                const u32 b = *reinterpret_cast<const __attribute__((address_space(3))) uint16_t*>(rd0 + (u32)(2 * p + 1) * 2u * Bl);
+                xb[p] = (a | (b << 16)) & xmask;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    // ---- the first two windows of this wave are requested before the tables are built
+    LaneChunk<BITS> c0[RG], c1[RG], c2[RG];
+    u32 xb[16], xv[16];
+    int t = dense ? wave : 0;                                        // wave w takes windows w, w + NWD, ... (NWD <= nwin)
+    const int last_t = t < nwin ? wave + ((nwin - 1 - wave) / NWD) * NWD : 0;   // this wave's last window
+    if (t < nwin) {
+        load_xblock(t, xv);
+        load_idx(t, c0);
+        load_idx(min(t + NWD, last_t), c1);
+    }
     __syncthreads();
     if (dense)
-        for (int u = wave; u < R; u += NW) build_tables<BITS, 1>(tables + u * TD, raw + u * K, lane);
+        for (int o = tid; o < R * TableShape<BITS>::kEntries; o += blockDim.x) {
+            // consecutive threads write consecutive rows of one entry (conflict-free); see entry_offsets for the layout
+            const int rho = o % R, e = o / R;
+            const uint16_t* rr = raw + rho * K;
+            if constexpr (BITS == 2) {
+                const u32 v0 = rr[e & 3], v1 = rr[(e >> 2) & 3], v2 = rr[(e >> 4) & 3], v3 = rr[e >> 6];
+                *reinterpret_cast<u32x2*>(tables + 2 * o) = u32x2{v0 | (v1 << 16), v2 | (v3 << 16)};
+            } else {
+                const u32 lo16 = rr[e & (K - 1)], hi16 = rr[e >> BITS];
+                tables[o] = lo16 | (hi16 << 16);
+            }
+        }
     __syncthreads();
 
     float4v_t acc[RG];
 #pragma unroll
     for (int rg = 0; rg < RG; ++rg) acc[rg] = float4v_t{0.f, 0.f, 0.f, 0.f};
 
-    // ---- dense term: windows t, t + NW, ...; the next window is requested before the current one is decoded
-    for (; t < nwin; t += NW) {
-        const int tn = t + NW < nwin ? t + NW : t;                   // the last window is requested twice rather than branching around loads
-        load_idx(tn, cn);
-        load_xb(tn, xn);
+    // ---- dense term: windows t, t + NW, ...  Indices are requested two windows ahead, activations one window ahead
+    //      (from L2) and staged while the matrix cores work on the current window.  Past the wave's last window the
+    //      requests repeat that window (valid addresses, results unused) instead of branching around loads.
+    if (t < nwin) {
+        stage_x(xv, xb);
+        load_xblock(min(t + NWD, last_t), xv);
+    }
+    for (; t < nwin; t += NWD) {
+        load_idx(min(t + 2 * NWD, last_t), c2);
         u32 w[2][16];
-        lookup_chunk<BITS>(c[0], tables + r * TD, w[0]);
+        lookup_chunk_at<BITS, kStrideLog2>(c0[0], tab0, w[0]);
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) {
-            if (rg + 1 < RG) lookup_chunk<BITS>(c[rg + 1], tables + (16 * (rg + 1) + r) * TD, w[(rg + 1) & 1]);
+            if (rg + 1 < RG) lookup_chunk_at<BITS, kStrideLog2>(c0[rg + 1], tab0 + 16u * (rg + 1) * kEntryBytes, w[(rg + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int m = 0; m < 8; ++m) {
@@ -935,14 +1182,15 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        stage_x(xv, xb);                                             // window t + NWD
+        load_xblock(min(t + 2 * NWD, last_t), xv);
 #pragma unroll
-        for (int rg = 0; rg < RG; ++rg) c[rg] = cn[rg];
-#pragma unroll
-        for (int p = 0; p < 16; ++p) xb[p] = xn[p];
+        for (int rg = 0; rg < RG; ++rg) { c0[rg] = c1[rg]; c1[rg] = c2[rg]; }
     }
 
-    // ---- sparse term: step j covers nonzeros [16 j, 16 j + 16); flat step f of the block = (row group, j)
-    if (sparse) {
+    // ---- sparse term, after the dense windows: every wave takes steps wave, wave + NW, ... of the block (a heavy row
+    //      is spread over all waves); rounds of 4 steps per wave, or of 8 while more than 4 NW steps are left
+    if (sparse_wave) {
         int first[RG], count[RG], total = 0;                         // uniform
 #pragma unroll
         for (int rg = 0; rg < RG; ++rg) {
@@ -951,55 +1199,18 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
             count[rg] = P1 > P0 ? ((P1 - 1) >> 4) - (P0 >> 4) + 1 : 0;
             total += count[rg];
         }
-        const int last_nz = (int)g.nnz - 1;
-        const uint16_t* __restrict__ vals = static_cast<const uint16_t*>(g.vals);
-        for (int f0 = wave; f0 < total; f0 += NW * kB16SparseSteps) {
-            int srg[kB16SparseSteps], sj[kB16SparseSteps];           // uniform: row group and step of each slot (-1: none)
-            u32 col[kB16SparseSteps], val[kB16SparseSteps];
-#pragma unroll
-            for (int k = 0; k < kB16SparseSteps; ++k) {
-                int f = f0 + k * NW;
-                srg[k] = -1; sj[k] = 0;
-                if (f < total) {
-#pragma unroll
-                    for (int rg = 0; rg < RG; ++rg) {
-                        if (srg[k] < 0) {
-                            if (f < count[rg]) { srg[k] = rg; sj[k] = first[rg] + f; }
-                            else f -= count[rg];
-                        }
-                    }
-                }
-                const int pl = min(16 * sj[k] + 4 * q + (lane & 3), last_nz);   // lane e of a quad fetches nonzero 16 j + 4 q + e
-                col[k] = (u32)g.cols[pl];
-                val[k] = vals[pl];
-            }
-            u32 xa[kB16SparseSteps][2], aa[kB16SparseSteps][2];
-#pragma unroll
-            for (int k = 0; k < kB16SparseSteps; ++k) {
-                const u32 c0 = quad_bcast<0>(col[k]), c1 = quad_bcast<1>(col[k]), c2 = quad_bcast<2>(col[k]), c3 = quad_bcast<3>(col[k]);
-                const u32 x0 = x[(size_t)c0 * B + nb], x1 = x[(size_t)c1 * B + nb], x2 = x[(size_t)c2 * B + nb], x3 = x[(size_t)c3 * B + nb];
-                xa[k][0] = (x0 | (x1 << 16)) & xmask;
-                xa[k][1] = (x2 | (x3 << 16)) & xmask;
-            }
-#pragma unroll
-            for (int k = 0; k < kB16SparseSteps; ++k) {
-                const int p0 = 16 * sj[k] + 4 * q;
-                int l = 0, h = 0;
-#pragma unroll
-                for (int rg = 0; rg < RG; ++rg) { if (srg[k] == rg) { l = lo[rg]; h = hi[rg]; } }
-                const u32 v0 = quad_bcast<0>(val[k]), v1 = quad_bcast<1>(val[k]), v2 = quad_bcast<2>(val[k]), v3 = quad_bcast<3>(val[k]);
-                const u32 a0 = (p0 + 0 >= l && p0 + 0 < h) ? v0 : 0u, a1 = (p0 + 1 >= l && p0 + 1 < h) ? v1 : 0u;
-                const u32 a2 = (p0 + 2 >= l && p0 + 2 < h) ? v2 : 0u, a3 = (p0 + 3 >= l && p0 + 3 < h) ? v3 : 0u;
-                aa[k][0] = a0 | (a1 << 16);
-                aa[k][1] = a2 | (a3 << 16);
-            }
-#pragma unroll
-            for (int k = 0; k < kB16SparseSteps; ++k) {
-                const half4v_t a = __builtin_bit_cast(half4v_t, u32x2{aa[k][0], aa[k][1]});
-                const half4v_t b = __builtin_bit_cast(half4v_t, u32x2{xa[k][0], xa[k][1]});
-#pragma unroll
-                for (int rg = 0; rg < RG; ++rg)
-                    if (srg[k] == rg) acc[rg] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, acc[rg], 0, 0, 0);   // uniform branch
+        int f0 = wave;
+        while (f0 < total) {
+            if (total - f0 > 4 * NW) {
+                B16SparseSlots<RG, 8> S;
+                b16_sparse_issue<RG, 8>(g, first, count, total, f0, NW, lane, S);
+                b16_sparse_finish<RG, 8>(x, B, nb, xmask, lane, lo, hi, S, acc);
+                f0 += 8 * NW;
+            } else {
+                B16SparseSlots<RG, 4> S;
+                b16_sparse_issue<RG, 4>(g, first, count, total, f0, NW, lane, S);
+                b16_sparse_finish<RG, 4>(x, B, nb, xmask, lane, lo, hi, S, acc);
+                f0 += 4 * NW;
             }
         }
     }
@@ -1009,7 +1220,7 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
     for (int rg = 0; rg < RG; ++rg) {
         const float v[4] = {acc[rg].x, acc[rg].y, acc[rg].z, acc[rg].w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) part[(wave * R + 16 * rg + 4 * q + e) * 16 + r] = v[e];
+        for (int e = 0; e < 4; ++e) reinterpret_cast<float*>(stage)[(16 * rg + 4 * q + e) * 16 + r] = v[e];
     }
     __syncthreads();
     uint16_t* __restrict__ y = static_cast<uint16_t*>(g.y);
@@ -1017,7 +1228,7 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
         const int row = o >> 4, n = o & 15;
         if (row < nrows && n < B) {
             float sum = 0.f;
-            for (int wv = 0; wv < NW; ++wv) sum += part[(wv * R + row) * 16 + n];
+            for (int wv = 0; wv < NW; ++wv) sum += reinterpret_cast<const float*>(stage0 + wv * kB16StageBytes)[row * 16 + n];
             const size_t yo = (size_t)(r0 + row) * B + n;
             if (g.accumulate) sum += half_bits_to_float(y[yo]);
             y[yo] = float_to_half_bits(sum);
@@ -1203,24 +1414,35 @@ static hipError_t launch_matvec_b4(const MatvecArgs& g, hipStream_t s) {
 #ifndef SQ_B16_RG2_MIN_M
 #define SQ_B16_RG2_MIN_M 8192
 #endif
-template <int BITS, int RG>
+template <int BITS, int RG, int B4>
 static hipError_t launch_matvec_b16_r(const MatvecArgs& g, hipStream_t s) {
     constexpr int R = 16 * RG;
     const int nwin = g.qidx ? g.N / 128 : 0;
     const int NW = nwin ? (nwin < SQ_B16_NW ? nwin : SQ_B16_NW) : 4;
-    const size_t lds = (size_t)R * TableShape<BITS>::kTableDwords * 4 + (size_t)R * (2 << BITS) + (size_t)NW * R * 64;
+    const size_t lds = (size_t)R * TableShape<BITS>::kTableDwords * 4 + (size_t)R * (2 << BITS) + (size_t)NW * kB16StageBytes;
     static bool raised = false;                                      // idempotent: a race only repeats the call
     if (!raised) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&matvec_b16_kernel<BITS, RG>), hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&matvec_b16_kernel<BITS, RG, B4>), hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((matvec_b16_kernel<BITS, RG>), dim3((g.M + R - 1) / R), dim3(NW * kWave), lds, s, g);
+    hipLaunchKernelGGL((matvec_b16_kernel<BITS, RG, B4>), dim3((g.M + R - 1) / R), dim3(NW * kWave), lds, s, g);
     return hipGetLastError();
+}
+template <int BITS, int RG>
+static hipError_t launch_matvec_b16_b(const MatvecArgs& g, hipStream_t s) {
+    // batches of exactly 4, 8, 12 or 16 columns: rows of x are whole 8-byte units and take the fast activation path
+    switch (g.B) {
+        case 4: return launch_matvec_b16_r<BITS, RG, 1>(g, s);
+        case 8: return launch_matvec_b16_r<BITS, RG, 2>(g, s);
+        case 12: return launch_matvec_b16_r<BITS, RG, 3>(g, s);
+        case 16: return launch_matvec_b16_r<BITS, RG, 4>(g, s);
+        default: return launch_matvec_b16_r<BITS, RG, 0>(g, s);
+    }
 }
 template <int BITS>
 static hipError_t launch_matvec_b16(const MatvecArgs& g, hipStream_t s) {
-    return g.M >= SQ_B16_RG2_MIN_M ? launch_matvec_b16_r<BITS, 2>(g, s) : launch_matvec_b16_r<BITS, 1>(g, s);
+    return g.M >= SQ_B16_RG2_MIN_M ? launch_matvec_b16_b<BITS, 2>(g, s) : launch_matvec_b16_b<BITS, 1>(g, s);
 }
 
 #ifndef SQ_B16_MIN_B
