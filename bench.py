@@ -43,6 +43,9 @@ WORKLOADS = {
     "llama65b_attn_3bit": ([(8192, 8192)], 3, 0.0045, (0.01, 0.30), 1),
     "llama65b_mlp_pair_3bit": ([(22016, 8192), (8192, 22016)], 3, 0.0045, (0.01, 0.30), 1),
     "llama65b_attn_3bit_batch4": ([(8192, 8192)], 3, 0.0045, (0.01, 0.30), 4),
+    "llama65b_attn_3bit_batch8": ([(8192, 8192)], 3, 0.0045, (0.01, 0.30), 8),
+    "llama65b_attn_3bit_batch16": ([(8192, 8192)], 3, 0.0045, (0.01, 0.30), 16),
+    "llama7b_mlp_pair_3bit_batch16": ([(11008, 4096), (4096, 11008)], 3, 0.0045, (0.10, 0.50), 16),
 }
 
 
@@ -299,18 +302,24 @@ def main():
     fp16_bytes = sum(M * N * 2 + (M + N) * 2 for M, N in shapes)
     fcopies = max(2, int(np.ceil(args.footprint_gb * 1e9 / fp16_bytes)))
     wring = [[(torch.randn(M, N, device="cuda", dtype=torch.float16) * 0.02) for _ in range(fcopies)] for M, N in shapes]
-    xs = [torch.randn(N, device="cuda", dtype=torch.float16) for M, N in shapes]
-    ys = [torch.zeros(M, device="cuda", dtype=torch.float16) for M, N in shapes]
+    # the baselines see the same batch: x[N][B] -> y[M][B] (torch.mv for one column, torch.mm for more)
+    xs = [torch.randn(N, B, device="cuda", dtype=torch.float16) for M, N in shapes]
+    ys = [torch.zeros(M, B, device="cuda", dtype=torch.float16) for M, N in shapes]
+    xv = [x[:, 0].contiguous() for x in xs]
+    yv = [y[:, 0].contiguous() for y in ys]
 
     def step_fp16_own(s):
         c = s % fcopies
         for k, (M, N) in enumerate(shapes):
-            sq.sqllm_fp16_gemv(M, N, 1, wring[k][c], xs[k], ys[k])
+            sq.sqllm_fp16_gemv(M, N, B, wring[k][c], xs[k], ys[k])
 
     def step_fp16_torch(s):
         c = s % fcopies
         for k in range(len(shapes)):
-            torch.mv(wring[k][c], xs[k], out=ys[k])
+            if B == 1:
+                torch.mv(wring[k][c], xv[k], out=yv[k])
+            else:
+                torch.mm(wring[k][c], xs[k], out=ys[k])
 
     fsteps = max(20, args.steps // 4)
     sec_f_own, _ = time_steps(torch, step_fp16_own, fsteps, 10, G)
@@ -364,7 +373,7 @@ def main():
                    "working_set_gb": step_bytes * copies / 1e9, "matvecs_per_step": len(shapes)},
         "effective_gbs": gbs, "pct_of_hbm_roofline": 100.0 * gbs / HBM_PEAK_GBS, "us_per_step": sec_cold / args.steps * 1e6,
         "warm_us_per_matvec": sec_warm / launches * 1e6, "warm_effective_gbs": step_bytes * args.steps / sec_warm / 1e9,
-        "fp16_gemv_us": {"own_kernel": us_f_own, "torch_mv": us_f_torch}, "speedup_vs_fp16": us_f / us_per_matvec,
+        "fp16_gemv_us": {"own_kernel": us_f_own, "torch_mv" if B == 1 else "torch_mm": us_f_torch}, "speedup_vs_fp16": us_f / us_per_matvec,
         "parity_worst_err_over_bound": worst, "launch_mode": "hip_graph_replay" if G else "python_ctypes", "host_wall_s_timed_region": wall_cold,
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                      "traffic": traffic, "kernel": f"sqllm::matvec_kernel<{bits},1,*>",

@@ -27,6 +27,9 @@
 //     scalar registers, and the products are combined per row with a segmented scan built from DPP moves.
 //     Only the last lane of each row segment touches the row's LDS accumulator, so no floating-point
 //     atomics are needed and the result does not depend on timing.
+// Batches: two activation columns go to matvec_b4_kernel, three to sixteen to matvec_b16_kernel -- both run the dense
+// term on the matrix cores (every lane decodes its own row, MFMAs replace the packed dot products); their headers
+// describe the lane mappings.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -1408,17 +1411,16 @@ static hipError_t launch_matvec_b4(const MatvecArgs& g, hipStream_t s) {
 }
 
 // up to 16 columns in one launch: 32 rows per workgroup when that still gives every compute unit a workgroup
-#ifndef SQ_B16_NW
-#define SQ_B16_NW 16
-#endif
-#ifndef SQ_B16_RG2_MIN_M
-#define SQ_B16_RG2_MIN_M 8192
-#endif
+// Measured (8192x8192, 11008x4096, 4096x4096, 22016x8192 at 16 columns): 8 waves per workgroup beat 16 (fused 23.4 / 22.2 /
+// 9.8 us against 24.3 / 27.6 / 11.0) and 4 (the sparse term then has too few waves); 32 rows per workgroup beat 16 from
+// M = 8192 on (dense 15.1 against 19.6 us: the activations a workgroup stages serve twice the rows).
+constexpr int kB16Waves = 8;
+constexpr int kB16TwoGroupsMinM = 8192;
 template <int BITS, int RG, int B4>
 static hipError_t launch_matvec_b16_r(const MatvecArgs& g, hipStream_t s) {
     constexpr int R = 16 * RG;
     const int nwin = g.qidx ? g.N / 128 : 0;
-    const int NW = nwin ? (nwin < SQ_B16_NW ? nwin : SQ_B16_NW) : 4;
+    const int NW = nwin ? (nwin < kB16Waves ? nwin : kB16Waves) : 4;
     const size_t lds = (size_t)R * TableShape<BITS>::kTableDwords * 4 + (size_t)R * (2 << BITS) + (size_t)NW * kB16StageBytes;
     static bool raised = false;                                      // idempotent: a race only repeats the call
     if (!raised) {
@@ -1442,15 +1444,14 @@ static hipError_t launch_matvec_b16_b(const MatvecArgs& g, hipStream_t s) {
 }
 template <int BITS>
 static hipError_t launch_matvec_b16(const MatvecArgs& g, hipStream_t s) {
-    return g.M >= SQ_B16_RG2_MIN_M ? launch_matvec_b16_b<BITS, 2>(g, s) : launch_matvec_b16_b<BITS, 1>(g, s);
+    return g.M >= kB16TwoGroupsMinM ? launch_matvec_b16_b<BITS, 2>(g, s) : launch_matvec_b16_b<BITS, 1>(g, s);
 }
 
-#ifndef SQ_B16_MIN_B
-#define SQ_B16_MIN_B 5
-#endif
 template <int BITS>
 static hipError_t launch_matvec_b(const MatvecArgs& g0, hipStream_t s) {
-    if (g0.qidx && g0.mfma_batch && (g0.B >= SQ_B16_MIN_B || g0.B == 3)) {
+    // a dense term and 3 or more columns: one launch of the 16-column kernel (at 4 columns 8192x8192 fused 20.4 against
+    // 22.3 us for the 4-column kernel, 4096x4096 8.0 against 9.5); two columns stay with the 4-column kernel
+    if (g0.qidx && g0.mfma_batch && g0.B >= 3) {
         MatvecArgs g = g0;
         g.bt0 = 0; g.bn = g0.B;
         return launch_matvec_b16<BITS>(g, s);
