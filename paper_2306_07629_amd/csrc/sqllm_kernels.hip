@@ -487,7 +487,7 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
     __shared__ float spart[(kMaxDenseWaves + 1) * R * NB];           // sparse: [wave][r][t]
     extern __shared__ __align__(16) char xstage[];                   // batched launches: W * XStage<NB, XG>::kBytes
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
     const int NW = blockDim.x >> 6;
     const bool dense = g.qidx != nullptr, sparse = g.nnz > 0;
     const int W = dense ? (g.N + kSliceCols - 1) / kSliceCols : 0;

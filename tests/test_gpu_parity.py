@@ -93,12 +93,46 @@ def test_small_layers_all_entry_points(M, N, bits, frac, skew, B):
         assert (np.abs(y2 - y_ref) <= TOL * a_ref).all()
 
 
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_every_batch_size(bits):
+    """B = 1 .. 16 on one small layer: the one-column kernel, the 4-column kernel (B = 2) and every activation path of
+    the 16-column kernel (4 / 8 / 12 / 16 columns: vector loads and in-register pairing; any other B: staged as it lies
+    in memory), fused, dense only and accumulating."""
+    M, N = 45, 384
+    for B in range(1, 17):
+        print(f"case bits={bits} B={B}", flush=True)
+        L = gen.make_layer(M, N, bits, frac=0.01, skew=(0.1, 0.5), B=B, seed=700 + 17 * bits + B)
+        D = _dev(L)
+        y_ref, a_ref = oracle.layer_matvec(L)
+        check_y(D.matvec().cpu().numpy().view(np.float16).astype(np.float64), y_ref, a_ref, N, f"fused B={B}")
+        yd, ad = oracle.layer_matvec(L, sparse=False)
+        check_y(D.lut_gemv().cpu().numpy().view(np.float16).astype(np.float64), yd, ad, N, f"dense B={B}")
+        y2 = D.lut_gemv(accumulate=1).cpu().numpy().view(np.float16).astype(np.float64)
+        assert (np.abs(y2 - 2 * yd) <= 2 * TOL * ad + 2.0 ** -24).all(), f"accumulate B={B}"
+
+
+@pytest.mark.parametrize("M,N,bits,B", [(8200, 128, 2, 8), (8200, 256, 4, 4), (8222, 128, 3, 12), (8193, 128, 3, 13)])
+def test_wide_batches_with_32_rows_per_workgroup(M, N, bits, B):
+    print(f"case M={M} N={N} bits={bits} B={B}", flush=True)
+    L = gen.make_layer(M, N, bits, frac=0.0045, skew=(0.01, 0.3), B=B, seed=4000 + M + bits + B)
+    D = _dev(L)
+    y_ref, a_ref = oracle.layer_matvec(L)
+    check_y(D.matvec().cpu().numpy().view(np.float16).astype(np.float64), y_ref, a_ref, N, "fused")
+
+
 def test_results_are_reproducible_run_to_run():
     L = gen.make_layer(512, 4096, 3, frac=0.0045, skew=(0.01, 0.3), seed=5)
     D = _dev(L)
     a = D.matvec().cpu().numpy().copy()
     for _ in range(3):
         assert np.array_equal(D.matvec().cpu().numpy(), a)
+    # the batched kernels keep a fixed summation order as well (no floating-point atomics anywhere)
+    for B in (2, 4, 7, 16):
+        Lb = gen.make_layer(300, 2048, 3, frac=0.0045, skew=(0.01, 0.3), B=B, seed=6)
+        Db = _dev(Lb)
+        a = Db.matvec().cpu().numpy().copy()
+        for _ in range(3):
+            assert np.array_equal(Db.matvec().cpu().numpy(), a)
 
 
 def test_degenerate_sparse_patterns():
