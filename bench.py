@@ -376,7 +376,8 @@ def main():
         "fp16_gemv_us": {"own_kernel": us_f_own, "torch_mv" if B == 1 else "torch_mm": us_f_torch}, "speedup_vs_fp16": us_f / us_per_matvec,
         "parity_worst_err_over_bound": worst, "launch_mode": "hip_graph_replay" if G else "python_ctypes", "host_wall_s_timed_region": wall_cold,
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-                     "traffic": traffic, "kernel": f"sqllm::matvec_kernel<{bits},1,*>",
+                     "traffic": traffic,
+                     "kernel": (f"sqllm::matvec_kernel<{bits},1,*>" if B == 1 else f"sqllm::matvec_b4_kernel<{bits},*>" if B == 2 else f"sqllm::matvec_b16_kernel<{bits},*>"),
                      "algorithmic_bytes_per_launch": step_bytes / len(shapes)},
         "cpu_baseline": cpu,
     }
