@@ -848,7 +848,7 @@ __device__ __forceinline__ u32 quad_bcast(u32 v) {
     return (u32)__builtin_amdgcn_mov_dpp((int)v, E * 0x55, 0xF, 0xF, true);   // quad_perm: every lane reads lane E of its quad
 }
 
-constexpr int kB16StageBytes = 16 * (256 + 16);           // one window of x for 16 columns: 16 planes of 64 row pairs (fast path), or the window as it lies in memory plus the shifts of its quarters (4224 bytes)
+constexpr int kB16StageBytes = 16 * 400;                  // one window of x for 16 columns: 16 planes of 64 row pairs (fast path), or the window as it lies in memory plus the shifts of its quarters (4224 bytes)
 
 // Entry-major tables.  Lane l of a 16-lane group decodes its OWN matrix row, so the 32 lanes the LDS serves together
 // read 32 different (row, entry) addresses; with one table after the other every row's entries overlay the same
@@ -1033,6 +1033,7 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
     constexpr int kStrideLog2 = (RG == 2 ? 5 : 4) + (kEntryBytes == 8 ? 3 : 2);   // log2(R * kEntryBytes): bytes from one entry to the next
     const u32 tab0 = (u32)r * kEntryBytes;                           // the lane's row of row group 0; the tables start at LDS address 0
     constexpr int BT = 4 * B4, kPitch = 256 + 16;                    // fast path: columns, bytes of one column's 64 row pairs (+ bank shift)
+    constexpr u32 kPitchQ = 400;                                     // plane pitch of the 8- and 16-column paths: 64 row pairs + up to 24 dwords of rotation
     auto load_xblock = [&](int t, u32 (&v)[16]) {
         if constexpr (B4 == 4 || B4 == 2) {
             // fully coalesced: load i of lane l is the 16-byte unit 64 i + l of the window (half a row of 16 columns, or
@@ -1068,8 +1069,15 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
             // the pair (x[k][n], x[k + 1][n]) of the even column n of each dword, the lane of the odd row that of the odd column
             const bool keven = B4 == 4 ? (lane & 2) == 0 : (lane & 1) == 0;
             const u32 sel = keven ? 0x05040100u : 0x03020706u;
-            const u32 wr = stage_lds + (B4 == 4 ? (u32)(8 * (lane & 1) + (keven ? 0 : 1)) * kPitch + (u32)(lane >> 2) * 4u
-                                                : (u32)(keven ? 0 : 1) * kPitch + (u32)(lane >> 1) * 4u);
+            // Plane n holds the 64 row pairs of column n, rotated by rot(n) dwords (planes of kPitchQ = 100 dwords, so a
+            // rotated plane needs no wrap-around).  The rotation makes BOTH sides conflict-free: the 32 lanes the LDS
+            // serves together write 8 (16) consecutive row pairs of 4 (2) planes whose bank offsets 4 n + rot(n) are 0, 8,
+            // 16, 24 (0, 16) apart, and 8 neighbouring lanes read 16 bytes of 8 planes whose offsets are the 8 multiples
+            // of 4.  Without it every write was a 4-way conflict (counters: 61 % of the LDS cycles).
+            //   16 columns: rot(n) = 4 + 4 [n%4 == 1] - 4 [n%4 == 2] + 16 [n >= 8];   8 columns: rot(n) = 12 - 4 (n / 2) + 12 (n % 2)
+            const u32 odd = keven ? 0u : 1u, h = (u32)lane & 1u;
+            const u32 wr = B4 == 4 ? stage_lds + (8u * h + odd) * kPitchQ + ((u32)(lane >> 2) + 4u * odd + 16u * h) * 4u
+                                   : stage_lds + odd * kPitchQ + ((u32)(lane >> 1) + 12u * odd) * 4u;
 #pragma unroll
             for (int i = 0; i < B4; ++i)
 #pragma unroll
@@ -1077,12 +1085,17 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
                     const u32 own = v[4 * i + d];
                     const u32 other = (u32)__builtin_amdgcn_mov_dpp((int)own, B4 == 4 ? 0x4E : 0xB1, 0xF, 0xF, true);   // quad_perm [2,3,0,1] / [1,0,3,2]
                     const u32 pair = __builtin_amdgcn_perm(other, own, sel);
-                    *reinterpret_cast<__attribute__((address_space(3))) u32*>(wr + (u32)(2 * d) * kPitch + (B4 == 4 ? 64u : 128u) * i) = pair;
+                    const u32 off = B4 == 4 ? (u32)(2 * d) * kPitchQ + 64u * i + 16u * (1 - (d & 1))
+                                            : (u32)(2 * d) * kPitchQ + 128u * i + 4u * (12 - 4 * d);
+                    *reinterpret_cast<__attribute__((address_space(3))) u32*>(wr + off) = pair;
                 }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            const u32 rd = stage_lds + (u32)nb * kPitch + (u32)q * 64u;
+            const u32 n3 = (u32)nb & 3u;
+            const u32 rot = B4 == 4 ? 4u + (n3 == 1u ? 4u : 0u) - (n3 == 2u ? 4u : 0u) + 16u * ((u32)nb >> 3)
+                                    : 12u - 4u * (((u32)nb & 7u) >> 1) + 12u * ((u32)nb & 1u);
+            const u32 rd = stage_lds + (u32)nb * kPitchQ + ((u32)q * 16u + rot) * 4u;
             const u32 xm = B4 == 4 ? 0xFFFFFFFFu : xmask;            // with 16 columns every lane's column exists
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
