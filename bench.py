@@ -139,6 +139,105 @@ CSR_ABLATION = {
 }
 
 
+# Full batch-1 decode step of a 7B-shaped model (the linear layers only): 32 blocks x (q, k, v, o 4096x4096; gate, up
+# 11008x4096; down 4096x11008), every one of the 224 layers with its own seeded weights resident in HBM (2.6 GB), one
+# step = the 224 matvecs back to back on one stream.
+DECODE_STEP = {
+    # name: (blocks, layer shapes of one block, bits, frac, skew)
+    "llama7b_decode_step_3bit": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 3, 0.0045, (0.10, 0.50)),
+    "llama7b_decode_step_4bit": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 4, 0.0045, (0.10, 0.50)),
+    # projections that share an input stacked row-wise (q,k,v -> 12288 rows; gate,up -> 22016 rows): 128 launches
+    "llama7b_decode_step_3bit_stacked": (32, [(12288, 4096), (4096, 4096), (22016, 4096), (4096, 11008)], 3, 0.0045, (0.10, 0.50)),
+}
+
+
+def bench_decode_step(args):
+    import numpy as np
+    import torch
+    import gen
+    import oracle   # parity gate and cpu_baseline leg only
+    import paper_2306_07629_amd as sq
+
+    blocks, shapes, bits, frac, skew = DECODE_STEP[args.workload]
+    checked = sorted({0, blocks // 2 - 1, blocks - 1})          # blocks whose layers are compared with the oracle
+    dev, step_bytes, worst, kept = [], 0, 0.0, []
+    t_gen = time.perf_counter()
+    for b in range(blocks):
+        for li, (M, N) in enumerate(shapes):
+            L = gen.make_layer(M, N, bits, frac=frac, skew=skew, B=1, seed=gen.layer_seed(SEED, 4, b * len(shapes) + li))
+            D = sq.DeviceLayer(L)
+            step_bytes += sq.sqllm_algorithmic_bytes(L.M, L.N, L.bits, L.nnz, 1)
+            if b in checked:
+                y = D.matvec().cpu().numpy().view(np.float16).astype(np.float64)
+                y_ref, absdot = oracle.layer_matvec(L)
+                ratio = float(np.max(np.abs(y - y_ref) / (2e-3 * absdot)))
+                if not (ratio <= 1.0):
+                    print(f"bench.py: parity FAILED for block {b} layer {li} ({M}x{N}): worst err/bound {ratio}", file=sys.stderr)
+                    sys.exit(4)
+                worst = max(worst, ratio)
+                if b == 0:
+                    kept.append(L)                             # the cpu_baseline sample
+            dev.append(D)
+            del L
+        print(f"bench.py: block {b + 1}/{blocks} generated and uploaded ({time.perf_counter() - t_gen:.0f} s)", file=sys.stderr, flush=True)
+    torch.cuda.synchronize()
+    n_layers = len(dev)
+
+    def step(_s):
+        for D in dev:
+            D.matvec()
+
+    G = not args.no_graph
+    sec, wall = time_steps(torch, step, args.steps, args.warmup, G)
+    us_step = sec / args.steps * 1e6
+    gbs = step_bytes * args.steps / sec / 1e9
+
+    # fp16 baseline: the same 224 shapes as fp16 matrices (13 GB), library GEMV and the own kernel
+    ws = [(torch.randn(M, N, device="cuda", dtype=torch.float16) * 0.02) for _ in range(blocks) for M, N in shapes]
+    xs = {N: torch.randn(N, device="cuda", dtype=torch.float16) for _, N in shapes}
+    ys = {M: torch.zeros(M, device="cuda", dtype=torch.float16) for M, _ in shapes}
+
+    def step_torch(_s):
+        for w in ws:
+            torch.mv(w, xs[w.shape[1]], out=ys[w.shape[0]])
+
+    def step_own(_s):
+        for w in ws:
+            sq.sqllm_fp16_gemv(w.shape[0], w.shape[1], 1, w, xs[w.shape[1]], ys[w.shape[0]])
+
+    fsteps = max(3, args.steps // 4)
+    us_torch = time_steps(torch, step_torch, fsteps, 1, G)[0] / fsteps * 1e6
+    us_own = time_steps(torch, step_own, fsteps, 1, G)[0] / fsteps * 1e6
+    del ws
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        times = []
+        for _ in range(3):
+            t0 = time.perf_counter()
+            for L in kept:
+                oracle.layer_matvec(L)
+            times.append(time.perf_counter() - t0)
+        med = sorted(times)[1]
+        cpu = {"value": med * blocks * 1e6, "unit": "us per token-equivalent", "cores": oracle.threads(), "kind": "oracle",
+               "sample": f"the {len(kept)} layers of block 0, median of 3 passes, scaled by {blocks} blocks; fp64, OpenMP over rows"}
+
+    print(json.dumps({
+        "metric": f"us per token-equivalent: the {n_layers} dense+sparse matvecs ({bits}-bit LUT + {100 * frac:g}% CSR) of the linear layers of a 7B-shaped decode step, back to back on one stream",
+        "value": us_step, "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": us_step * 1e-3,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "blocks": blocks, "layers_per_block": [f"{M}x{N}" for M, N in shapes], "bits": bits, "sparse_frac": frac,
+                   "skew": skew, "batch": 1, "seed": SEED, "distinct_layers_resident": n_layers, "resident_gb": step_bytes / 1e9,
+                   "parity_checked_blocks": checked, "matvecs_per_step": n_layers},
+        "us_per_matvec": us_step / n_layers, "effective_gbs": gbs, "pct_of_hbm_roofline": 100.0 * gbs / HBM_PEAK_GBS,
+        "fp16_step_us": {"own_kernel": us_own, "torch_mv": us_torch}, "speedup_vs_fp16": min(us_own, us_torch) / us_step,
+        "parity_worst_err_over_bound": worst, "launch_mode": "hip_graph_replay" if G else "python_ctypes", "host_wall_s_timed_region": wall,
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": f"sqllm::matvec_kernel<{bits},1,*>", "algorithmic_bytes_per_launch": step_bytes / n_layers},
+        "cpu_baseline": cpu,
+    }))
+
+
 def bench_csr_ablation(args):
     import numpy as np
     import torch
@@ -188,7 +287,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", default="llama7b_mlp_pair_3bit", choices=sorted(WORKLOADS) + sorted(QUANT_WORKLOADS) + sorted(CSR_ABLATION))
+    ap.add_argument("--workload", default="llama7b_mlp_pair_3bit", choices=sorted(WORKLOADS) + sorted(QUANT_WORKLOADS) + sorted(CSR_ABLATION) + sorted(DECODE_STEP))
     ap.add_argument("--footprint-gb", type=float, default=1.1, help="bytes of distinct weight copies to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rows-per-wg", type=int, default=0)
@@ -253,6 +352,10 @@ def main():
         if args.steps == 400 and args.warmup == 40:
             args.steps, args.warmup = 200, 20
         return bench_csr_ablation(args)
+    if args.workload in DECODE_STEP:
+        if args.steps == 400 and args.warmup == 40:
+            args.steps, args.warmup = 20, 3
+        return bench_decode_step(args)
     if args.workload in QUANT_WORKLOADS:
         if args.steps == 400 and args.warmup == 40:     # the defaults are sized for the microsecond matvecs
             args.steps, args.warmup = 20, 3
