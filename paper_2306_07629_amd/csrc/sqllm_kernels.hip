@@ -1469,9 +1469,10 @@ static hipError_t launch_matvec_b(const MatvecArgs& g0, hipStream_t s) {
         g.bt0 = 0; g.bn = g0.B;
         return launch_matvec_b16<BITS>(g, s);
     }
-    // Batch columns are processed in windows: 4 (or 2) columns per launch when the batch is even -- their
-    // activations must fit in registers -- and one column per launch when it is odd (rows of x are then not
-    // dword aligned).  B = 1, 2 and 4 are single launches.
+    // Everything else -- one column, two columns, calls without a dense term, and calls under an explicit
+    // rows-per-workgroup request -- goes in windows: 4 (or 2) columns per launch when the batch is even (their
+    // activations must fit in registers) and one column per launch when it is odd (rows of x are then not dword
+    // aligned).  B = 1, 2 and 4 are single launches.
     const int step = g0.B == 1 ? 1 : ((g0.B & 1) ? 1 : 4);
     for (int t0 = 0; t0 < g0.B; t0 += step) {
         MatvecArgs g = g0;
