@@ -81,8 +81,8 @@ int sqllm_csr_spmv(int M, int N, long long nnz, int B,
 /* Both terms in ONE kernel launch (Sec. 4.3: dense and sparse kernels are launched in one call so that no
  * separate pass sums their outputs):  y = fp16( D x + S x ), summed in fp32.  nnz == 0 -> dense only.
  * B = 1 is the paper's matrix-vector case; B = 2..16 is still one launch (the products then run on the
- * matrix cores, every weight is decoded once for all columns).  A sparse-only call (sqllm_csr_spmv) with
- * B > 1 takes one launch per window of four columns (per column when B is odd).                          */
+ * matrix cores, every weight is decoded once for all columns), also for the dense-only and the sparse-only
+ * entry points.                                                                                          */
 int sqllm_dense_sparse_matvec(int M, int N, int bits, long long nnz, int B,
                               const void* qidx, const void* lut,
                               const int* rowptr, const int* cols, const void* vals,

@@ -1433,7 +1433,7 @@ template <int BITS, int RG, int B4>
 static hipError_t launch_matvec_b16_r(const MatvecArgs& g, hipStream_t s) {
     constexpr int R = 16 * RG;
     const int nwin = g.qidx ? g.N / 128 : 0;
-    const int NW = nwin ? (nwin < kB16Waves ? nwin : kB16Waves) : 4;
+    const int NW = nwin ? (nwin < kB16Waves ? nwin : kB16Waves) : kB16Waves;   // without a dense term all waves share the sparse steps
     const size_t lds = (size_t)R * TableShape<BITS>::kTableDwords * 4 + (size_t)R * (2 << BITS) + (size_t)NW * kB16StageBytes;
     static bool raised = false;                                      // idempotent: a race only repeats the call
     if (!raised) {
@@ -1462,9 +1462,9 @@ static hipError_t launch_matvec_b16(const MatvecArgs& g, hipStream_t s) {
 
 template <int BITS>
 static hipError_t launch_matvec_b(const MatvecArgs& g0, hipStream_t s) {
-    // a dense term and 3 or more columns: one launch of the 16-column kernel (at 4 columns 8192x8192 fused 20.4 against
-    // 22.3 us for the 4-column kernel, 4096x4096 8.0 against 9.5); two columns stay with the 4-column kernel
-    if (g0.qidx && g0.mfma_batch && g0.B >= 3) {
+    // 3 or more columns: one launch of the 16-column kernel, with or without a dense term (at 4 columns 8192x8192 fused
+    // 20.4 against 22.3 us for the 4-column kernel, 4096x4096 8.0 against 9.5); two columns stay with the 4-column kernel
+    if (g0.mfma_batch && g0.B >= 3) {
         MatvecArgs g = g0;
         g.bt0 = 0; g.bn = g0.B;
         return launch_matvec_b16<BITS>(g, s);
