@@ -78,7 +78,7 @@ def test_config5_llama65b_heavy_skew(M, N):
     run_layer(M, N, 3, 0.0045, (0.01, 0.30), 1, gen.layer_seed(SEED, 5, M // 1000 + N // 100))
 
 
-@pytest.mark.parametrize("B", [2, 4])
+@pytest.mark.parametrize("B", [2, 4, 8, 16])
 def test_config5_batched(B):
     run_layer(8192, 8192, 3, 0.0045, (0.01, 0.30), B, gen.layer_seed(SEED, 5, 100 + B))
 
@@ -89,7 +89,7 @@ def test_ragged_row_counts(M, bits):
     run_layer(M, 4096, bits, 0.0045, None, 1, 77 + M, check_decode_rows=M)
 
 
-@pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 6, 7, 8, 11, 16])
 def test_every_batch_size(B):
     run_layer(70, 2304, 3, 0.0045, (0.1, 0.5), B, 500 + B, check_decode_rows=70)
     run_layer(70, 2304, 4, 0.0045, (0.1, 0.5), B, 600 + B, check_decode_rows=70)
@@ -98,6 +98,8 @@ def test_every_batch_size(B):
 def test_widest_supported_row():
     run_layer(9, 28672, 3, 0.0045, None, 1, 901, check_decode_rows=9)
     run_layer(9, 28672, 4, 0.0045, None, 2, 902, check_decode_rows=9)
+    run_layer(9, 28672, 3, 0.0045, None, 16, 903, check_decode_rows=9)
+    run_layer(40, 28672, 2, 0.0045, (0.1, 0.5), 9, 904, check_decode_rows=40)
 
 
 def test_one_row_holds_every_nonzero_of_a_big_block():

@@ -62,7 +62,7 @@ def test_non_default_stream_and_back_to_back_calls():
     assert torch.equal(D.y, base)
 
 
-@pytest.mark.parametrize("bits,M,N,B", [(3, 37, 2176, 1), (4, 70, 4096, 2), (3, 9, 11008, 4)])
+@pytest.mark.parametrize("bits,M,N,B", [(3, 37, 2176, 1), (4, 70, 4096, 2), (3, 9, 11008, 4), (3, 40, 2176, 16), (4, 33, 384, 7), (2, 50, 1024, 12)])
 def test_guard_regions_around_outputs_stay_untouched(bits, M, N, B):
     """y, idx_out and w_out are carved out of larger buffers filled with a sentinel"""
     import torch
@@ -97,8 +97,9 @@ def test_inputs_at_the_very_end_of_an_allocation():
     rows are clamped, never read past the end); checked for correctness of the result"""
     import torch
     import paper_2306_07629_amd as sq
-    for bits, M, N in [(3, 5, 2176), (4, 3, 128), (3, 2, 28672), (2, 5, 2176), (2, 1, 128)]:
-        L = gen.make_layer(M, N, bits, frac=0.0045, seed=60 + M)
+    for bits, M, N, B in [(3, 5, 2176, 1), (4, 3, 128, 1), (3, 2, 28672, 1), (2, 5, 2176, 1), (2, 1, 128, 1),
+                          (3, 5, 2176, 16), (4, 19, 128, 5), (2, 33, 256, 8), (3, 17, 384, 3)]:
+        L = gen.make_layer(M, N, bits, frac=0.0045, B=B, seed=60 + M + B)
         D = sq.DeviceLayer(L)          # torch allocates each array exactly as large as its contents
         y = _f64(D.matvec())
         y_ref, absdot = oracle.layer_matvec(L)
