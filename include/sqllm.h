@@ -33,6 +33,10 @@
  *   synchronises: each call validates its arguments on the host, enqueues kernels on `stream`
  *   (a hipStream_t passed as void*, NULL = the default stream) and returns.  Device-side data (index
  *   ranges of cols, monotonicity of rowptr) is NOT validated; out-of-range columns are undefined behaviour.
+ *   Finiteness is not validated either.  A non-finite activation x[j][t] reaches y[i][t] wherever the
+ *   definition multiplies it by a weight (every row, through the dense term); in calls with B >= 3 the sparse
+ *   term is formed by matrix instructions over groups of 16 rows, and a non-finite x[j][t] then also turns
+ *   y[i][t] into NaN for the other rows of the group of a row holding a nonzero in column j (0 x Inf).
  *
  * ERRORS  every function returns an sqllm_status; nothing is enqueued unless SQLLM_OK is returned.  A text
  *   for the last error of the calling thread is available from sqllm_last_error_string().
