@@ -478,7 +478,6 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
     static_assert(D >= 2 && D <= R, "prefetch depth");
     constexpr int E = TableShape<BITS>::kEntries, K = 1 << BITS;
     constexpr int kRawUnit = TableShape<BITS>::kRawUnit;             // bytes of fp16 tables one lane fetches (16, or 8 for b = 2)
-    constexpr int kRawLanes = R * TableShape<BITS>::kRowBytes / kRawUnit;
     constexpr int UB = 8;                                            // sparse batches per wave and round
     constexpr int TD = TableShape<BITS>::kTableDwords;
     __shared__ __align__(8) u32 tables[R * TD];
@@ -505,11 +504,17 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
 
     if (wave < W) {
         // ---- dense wave.  Issue order: (wave 0: fp16 tables), activations, first D rows of the index stream.
+        // b = 2: every dense wave fetches and builds the tables of rows wave, wave + W, ... -- one wave building all R
+        // tables (2 KB each) was a serial stretch before the barrier (8192x8192 fused 10.3 -> 9.7 us, 11008x4096 8.4 -> 8.0);
+        // b = 3, 4: wave 0 builds them all (splitting measured 1-2 % slower there).
+        constexpr bool kSplitBuild = BITS == 2;
+        constexpr int LPR = TableShape<BITS>::kRowBytes / kRawUnit;   // lanes fetching one row's fp16 table
+        const int my_rows = kSplitBuild ? (R - wave + W - 1) / W : (wave == 0 ? R : 0);
+        const int bu = kSplitBuild ? wave + (lane / LPR) * W : lane / LPR;   // row of the block this lane fetches a piece of
         u32x4 rawv = {0, 0, 0, 0};
-        if (wave == 0 && lane < kRawLanes) {
-            const int u = lane * kRawUnit / TableShape<BITS>::kRowBytes;
-            const int row = min(r0 + u, g.M - 1);
-            const char* src = static_cast<const char*>(g.lut) + (size_t)row * TableShape<BITS>::kRowBytes + (lane * kRawUnit) % TableShape<BITS>::kRowBytes;
+        if (lane < my_rows * LPR) {
+            const int row = min(r0 + bu, g.M - 1);
+            const char* src = static_cast<const char*>(g.lut) + (size_t)row * TableShape<BITS>::kRowBytes + (lane % LPR) * kRawUnit;
             if constexpr (kRawUnit == 16) {
                 rawv = *reinterpret_cast<const u32x4*>(src);
             } else {
@@ -534,15 +539,19 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
 #pragma unroll
                 for (int p = 0; p < 16; ++p) xr[t][p] = 0;
         }
-        if (wave == 0) {
-            if (lane < kRawLanes) {
-                if constexpr (kRawUnit == 16) *reinterpret_cast<u32x4*>(raw + lane * 8) = rawv;
-                else *reinterpret_cast<u32x2*>(raw + lane * 4) = u32x2{rawv.x, rawv.y};
+        if (my_rows > 0) {                                            // uniform
+            if (lane < my_rows * LPR) {
+                if constexpr (kRawUnit == 16) *reinterpret_cast<u32x4*>(raw + bu * K + (lane % LPR) * 8) = rawv;
+                else *reinterpret_cast<u32x2*>(raw + bu * K) = u32x2{rawv.x, rawv.y};
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            build_tables<BITS, R>(tables, raw, lane);
+            if constexpr (kSplitBuild) {
+                for (int u = wave; u < R; u += W) build_tables<BITS, 1>(tables + u * TD, raw + u * K, lane);
+            } else {
+                build_tables<BITS, R>(tables, raw, lane);
+            }
         }
         __syncthreads();
         // software pipeline: the look-ups of row u + 1 are in flight while the products of row u are formed;
