@@ -42,6 +42,7 @@ WORKLOADS = {
     "llama7b_block_3bit_stacked": ([(12288, 4096), (4096, 4096), (22016, 4096), (4096, 11008)], 3, 0.0045, (0.10, 0.50), 1),
     "llama65b_attn_3bit": ([(8192, 8192)], 3, 0.0045, (0.01, 0.30), 1),
     "llama65b_mlp_pair_3bit": ([(22016, 8192), (8192, 22016)], 3, 0.0045, (0.01, 0.30), 1),
+    "llama65b_attn_3bit_batch2": ([(8192, 8192)], 3, 0.0045, (0.01, 0.30), 2),
     "llama65b_attn_3bit_batch4": ([(8192, 8192)], 3, 0.0045, (0.01, 0.30), 4),
     "llama65b_attn_3bit_batch8": ([(8192, 8192)], 3, 0.0045, (0.01, 0.30), 8),
     "llama65b_attn_3bit_batch16": ([(8192, 8192)], 3, 0.0045, (0.01, 0.30), 16),
@@ -401,6 +402,20 @@ def main():
     us_per_matvec = sec_cold / launches * 1e6
     gbs = step_bytes * args.steps / sec_cold / 1e9
 
+    # ---- single-launch latency: an event pair around ONE launch of the first layer after the device went idle
+    # (cold copy each time), median of 15; contains what a back-to-back stream hides: launch ramp, first data, drain
+    singles = []
+    for i in range(15):
+        torch.cuda.synchronize()
+        time.sleep(0.002)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ring[0][(i + 1) % copies].matvec()
+        e1.record()
+        torch.cuda.synchronize()
+        singles.append(e0.elapsed_time(e1) * 1e3)
+    single_launch_us = sorted(singles)[len(singles) // 2]
+
     # ---- fp16 baselines on the same shapes (own kernel and the vendor library through torch), cold as well
     fp16_bytes = sum(M * N * 2 + (M + N) * 2 for M, N in shapes)
     fcopies = max(2, int(np.ceil(args.footprint_gb * 1e9 / fp16_bytes)))
@@ -480,12 +495,13 @@ def main():
                    "skew": skew, "batch": B, "seed": SEED, "storage": "fp16 tables / CSR values / x / y, fp32 accumulation", "weight_copies_rotated": copies,
                    "working_set_gb": step_bytes * copies / 1e9, "matvecs_per_step": len(shapes)},
         "effective_gbs": gbs, "pct_of_hbm_roofline": 100.0 * gbs / HBM_PEAK_GBS, "us_per_step": sec_cold / args.steps * 1e6,
+        "single_launch_after_idle_us": single_launch_us,
         "warm_us_per_matvec": sec_warm / launches * 1e6, "warm_effective_gbs": step_bytes * args.steps / sec_warm / 1e9,
         "fp16_gemv_us": {"own_kernel": us_f_own, "torch_mv" if B == 1 else "torch_mm": us_f_torch}, "speedup_vs_fp16": us_f / us_per_matvec,
         "parity_worst_err_over_bound": worst, "launch_mode": "hip_graph_replay" if G else "python_ctypes", "host_wall_s_timed_region": wall_cold,
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                      "traffic": traffic,
-                     "kernel": (f"sqllm::matvec_kernel<{bits},1,*>" if B == 1 else f"sqllm::matvec_b4_kernel<{bits},*>" if B == 2 else f"sqllm::matvec_b16_kernel<{bits},*>"),
+                     "kernel": f"sqllm::matvec_kernel<{bits},1,*>" if B == 1 else f"sqllm::matvec_b16_kernel<{bits},*>",
                      "algorithmic_bytes_per_launch": step_bytes / len(shapes)},
         "cpu_baseline": cpu,
     }

@@ -27,9 +27,9 @@
 //     scalar registers, and the products are combined per row with a segmented scan built from DPP moves.
 //     Only the last lane of each row segment touches the row's LDS accumulator, so no floating-point
 //     atomics are needed and the result does not depend on timing.
-// Batches: two activation columns go to matvec_b4_kernel, three to sixteen to matvec_b16_kernel -- both run the dense
-// term on the matrix cores (every lane decodes its own row, MFMAs replace the packed dot products); their headers
-// describe the lane mappings.
+// Batches: two to sixteen activation columns go to matvec_b16_kernel, which runs the dense and the sparse term on the
+// matrix cores (every lane decodes its own row, MFMAs replace the packed dot products); its header describes the
+// lane mapping.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -625,214 +625,6 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
     }
 }
 
-// ---------------------------------------------------------------------------------------------- four activation columns on the matrix cores
-// With four activation columns the dense term is a small matrix product, and v_mfma_f32_4x4x4_16b_f16 fits it
-// exactly: the instruction multiplies, in each of its 16 blocks of four lanes, a 4 x 4 tile A (lane i supplies row i:
-// four consecutive k) by a 4 x 4 tile B (lane j supplies column j) and accumulates the 4 x 4 result (lane j keeps
-// column j).  Mapping:  lane l = 4 b + i of a dense wave owns the 32-column chunk b of the wave's slice and, for the
-// A operand, matrix row (4 rg + i) of the workgroup's row group rg; for the B operand it owns activation column i.
-//   * per row group and sub-slice a lane loads the 32 indices of ITS row (the wave reads four 192 / 256-byte row
-//     segments), turns them into 16 table offsets and 16 look-ups in ITS row's pair table -- the same decode as
-//     with one column -- and issues 8 MFMAs (four weights x four activations of all four columns each) instead of
-//     64 packed dot products;
-//   * the lane's 32 activations of column i come once per workgroup through a wave-private LDS transposition
-//     (coalesced loads of two x rows, pairs (x[2m][j], x[2m+1][j]) written to plane j, 64-byte reads back);
-//   * the accumulators (4 rows x column i) are summed over the 16 blocks with lane permutes at the very end.
-// A wave covers XS sub-slices of 512 columns (XS = 1, 2 or 4 by N), a workgroup G = 4 (or 2) row groups of 4 rows.
-// Windows of two columns use the same kernel with the other two columns zero.
-// Two sparse waves (UB batches each) and the final combination work as in the one-column kernel, with NB = 4.
-typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
-typedef float float4_t __attribute__((ext_vector_type(4)));
-
-constexpr int kPlaneBytes = 1024 + 16;                    // 256 activation pairs of one column, plus a bank shift
-constexpr int kXPlanesBytes = 4 * kPlaneBytes;            // per dense wave
-
-template <int BITS, int G, int XS>
-__global__ void __launch_bounds__(1024) matvec_b4_kernel(MatvecArgs g) {
-    constexpr int NB = 4, R = 4 * G, K = 1 << BITS, UB = 8;
-    constexpr int TD = TableShape<BITS>::kTableDwords;
-    constexpr int kRawUnit = TableShape<BITS>::kRawUnit;
-    constexpr int kRawLanes = R * TableShape<BITS>::kRowBytes / kRawUnit;
-    constexpr int kSubCols = 512;                                    // columns of one sub-slice (16 chunks of 32)
-    constexpr int kSparseWaves = 2;
-    __shared__ __align__(8) u32 tables[R * TD];
-    __shared__ __align__(16) uint16_t raw[R * K];
-    __shared__ float part[kMaxDenseWaves * R * NB];                  // [wave][row][column]
-    __shared__ float spart[(kMaxDenseWaves + 2) * R * NB];
-    extern __shared__ __align__(16) char xplanes[];                  // W * kXPlanesBytes
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int NW = blockDim.x >> 6;
-    const bool sparse = g.nnz > 0;
-    const int W = (g.N + kSubCols * XS - 1) / (kSubCols * XS);
-    const int r0 = blockIdx.x * R;
-    const int nrows = min(R, g.M - r0);
-    const int B = g.B, bn = g.bn;
-    const uint16_t* __restrict__ x = static_cast<const uint16_t*>(g.x) + g.bt0;
-
-    int rp[R + 1];
-    SparseRange sr;
-    load_row_pointers<NB, R>(g, r0, nrows, sparse, rp, sr);
-    float* myslots = spart + wave * R * NB;
-    if (lane < R * NB) myslots[lane] = 0.f;
-    int next_batch = 0;
-
-    if (wave < W) {
-        const int b = lane >> 2, i = lane & 3;
-        // ---- fp16 tables (wave 0), then activations, then the first index chunks
-        u32x4 rawv = {0, 0, 0, 0};
-        if (wave == 0 && lane < kRawLanes) {
-            const int u = lane * kRawUnit / TableShape<BITS>::kRowBytes;
-            const int row = min(r0 + u, g.M - 1);
-            const char* src = static_cast<const char*>(g.lut) + (size_t)row * TableShape<BITS>::kRowBytes + (lane * kRawUnit) % TableShape<BITS>::kRowBytes;
-            if constexpr (kRawUnit == 16) {
-                rawv = *reinterpret_cast<const u32x4*>(src);
-            } else {
-                const u32x2 v = *reinterpret_cast<const u32x2*>(src);
-                rawv.x = v.x; rawv.y = v.y;
-            }
-        }
-        // activations: xr[s][p] = (x[c + 2p][i], x[c + 2p + 1][i]) for the lane's chunk c = column of (sub-slice s, chunk b)
-        u32 xr[XS][16];
-        char* planes = xplanes + wave * kXPlanesBytes;
-#pragma unroll
-        for (int s = 0; s < XS; ++s) {
-            const int c0 = (wave * XS + s) * kSubCols;
-            u32 v0[4][2], v1[4][2];
-            const int off1 = bn > 2 ? 1 : 0;                         // a window of two columns is one dword per row: never read past it
-            if (B == 4) {
-                // rows of x are 8 bytes: a pair of rows is one aligned 16-byte load (N is even, so the pair is in range or not as a whole)
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int ra = min(c0 + 2 * (t * 64 + lane), g.N - 2);
-                    const u32x4 v = *reinterpret_cast<const u32x4*>(x + (size_t)ra * 4);
-                    v0[t][0] = v.x; v0[t][1] = v.y; v1[t][0] = v.z; v1[t][1] = v.w;
-                }
-            } else if (bn > 2 && (B & 3) == 0) {
-                // the window of a row is one aligned 8-byte load
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int ra = min(c0 + 2 * (t * 64 + lane), g.N - 2);
-                    const u32x2 a = *reinterpret_cast<const u32x2*>(x + (size_t)ra * B), bq = *reinterpret_cast<const u32x2*>(x + (size_t)(ra + 1) * B);
-                    v0[t][0] = a.x; v0[t][1] = a.y; v1[t][0] = bq.x; v1[t][1] = bq.y;
-                }
-            } else {
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int ra = min(c0 + 2 * (t * 64 + lane), g.N - 1), rb = min(c0 + 2 * (t * 64 + lane) + 1, g.N - 1);
-                    const u32* pa = reinterpret_cast<const u32*>(x + (size_t)ra * B);
-                    const u32* pb = reinterpret_cast<const u32*>(x + (size_t)rb * B);
-                    v0[t][0] = pa[0]; v1[t][0] = pb[0];
-                    v0[t][1] = pa[off1]; v1[t][1] = pb[off1];        // columns >= bn are zeroed below
-                }
-            }
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int m = t * 64 + lane;
-                *reinterpret_cast<u32*>(planes + 0 * kPlaneBytes + m * 4) = __builtin_amdgcn_perm(v1[t][0], v0[t][0], 0x05040100u);
-                *reinterpret_cast<u32*>(planes + 1 * kPlaneBytes + m * 4) = __builtin_amdgcn_perm(v1[t][0], v0[t][0], 0x07060302u);
-                *reinterpret_cast<u32*>(planes + 2 * kPlaneBytes + m * 4) = __builtin_amdgcn_perm(v1[t][1], v0[t][1], 0x05040100u);
-                *reinterpret_cast<u32*>(planes + 3 * kPlaneBytes + m * 4) = __builtin_amdgcn_perm(v1[t][1], v0[t][1], 0x07060302u);
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            const bool live = c0 + b * 32 < g.N && i < bn;
-            const u32x4* src = reinterpret_cast<const u32x4*>(planes + i * kPlaneBytes + b * 64);
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const u32x4 v = src[k];
-                xr[s][4 * k + 0] = live ? v.x : 0u; xr[s][4 * k + 1] = live ? v.y : 0u; xr[s][4 * k + 2] = live ? v.z : 0u; xr[s][4 * k + 3] = live ? v.w : 0u;
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        }
-        // index chunks: iteration it = rg * XS + s; the lane reads row (4 rg + i), chunk ((wave XS + s) 16 + b)
-        const size_t row_dwords = (size_t)g.N * BITS / 32;
-        const int last_chunk = g.N / 32 - 1;
-        constexpr int ITER = G * XS;
-        auto chunk_ptr = [&](int it) {
-            const int rg = it / XS, s = it % XS;
-            const int row = min(r0 + 4 * rg + i, g.M - 1);
-            const int cc = min((wave * XS + s) * 16 + b, last_chunk);
-            return static_cast<const u32*>(g.qidx) + (size_t)row * row_dwords + (size_t)cc * BITS;
-        };
-        LaneChunk<BITS> c[ITER];
-        constexpr int DP = ITER < 4 ? ITER : 4;                      // chunks requested ahead
-#pragma unroll
-        for (int it = 0; it < DP; ++it) c[it] = load_chunk<BITS>(chunk_ptr(it));
-        if (wave == 0) {
-            if (lane < kRawLanes) {
-                if constexpr (kRawUnit == 16) *reinterpret_cast<u32x4*>(raw + lane * 8) = rawv;
-                else *reinterpret_cast<u32x2*>(raw + lane * 4) = u32x2{rawv.x, rawv.y};
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            build_tables<BITS, R>(tables, raw, lane);
-        }
-        __syncthreads();
-        float4_t acc[G];
-#pragma unroll
-        for (int rg = 0; rg < G; ++rg) acc[rg] = float4_t{0.f, 0.f, 0.f, 0.f};
-        u32 w[2][16];
-        lookup_chunk<BITS>(c[0], tables + (0 * 4 + i) * TD, w[0]);
-        if constexpr (DP < ITER) c[DP] = load_chunk<BITS>(chunk_ptr(DP));
-#pragma unroll
-        for (int it = 0; it < ITER; ++it) {
-            if (it + 1 < ITER) {
-                lookup_chunk<BITS>(c[it + 1], tables + (((it + 1) / XS) * 4 + i) * TD, w[(it + 1) & 1]);
-                if (it + 1 + DP < ITER) c[it + 1 + DP] = load_chunk<BITS>(chunk_ptr(it + 1 + DP));
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            const int rg = it / XS, s = it % XS;
-#pragma unroll
-            for (int m = 0; m < 8; ++m) {
-                const half4_t a = __builtin_bit_cast(half4_t, u32x2{w[it & 1][2 * m], w[it & 1][2 * m + 1]});
-                const half4_t bb = __builtin_bit_cast(half4_t, u32x2{xr[s][2 * m], xr[s][2 * m + 1]});
-                acc[rg] = __builtin_amdgcn_mfma_f32_4x4x4f16(a, bb, acc[rg], 0, 0, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // sum over the 16 blocks of the wave (lanes with the same column i), then lanes 0..3 hold the slice sums
-#pragma unroll
-        for (int rg = 0; rg < G; ++rg) {
-            float v[4] = {acc[rg].x, acc[rg].y, acc[rg].z, acc[rg].w};
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                v[r] += __shfl_xor(v[r], 4, 64); v[r] += __shfl_xor(v[r], 8, 64); v[r] += __shfl_xor(v[r], 16, 64); v[r] += __shfl_xor(v[r], 32, 64);
-                if (lane < 4) part[(wave * R + rg * 4 + r) * NB + lane] = v[r];
-            }
-        }
-        next_batch = kSparseWaves * UB;
-    } else {
-        __syncthreads();                                              // the dense waves' table barrier
-        // two sparse waves, UB batches each: 16 rows carry about 10 batches at 0.45 %
-        const int b0 = (wave - W) * UB;
-        if (sr.nbatch > b0 + 2) sparse_round<NB, R, UB>(g, x, sr, rp, b0, 1, lane, myslots);
-        else if (sr.nbatch > b0) sparse_round<NB, R, 2>(g, x, sr, rp, b0, 1, lane, myslots);
-        next_batch = kSparseWaves * UB;
-    }
-    for (int b0 = next_batch + wave; b0 < sr.nbatch; b0 += NW * UB)   // uniform
-        sparse_round<NB, R, UB>(g, x, sr, rp, b0, NW, lane, myslots);
-    __syncthreads();
-
-    uint16_t* __restrict__ y = static_cast<uint16_t*>(g.y) + g.bt0;
-    if (tid < nrows * NB) {
-        const int r = tid / NB, t = tid - r * NB;
-        if (t < bn) {
-            float sum = 0.f;
-            for (int wv = 0; wv < W; ++wv) sum += part[(wv * R + r) * NB + t];
-            if (sparse)
-                for (int wv = 0; wv < NW; ++wv) sum += spart[(wv * R + r) * NB + t];
-            const size_t o = (size_t)(r0 + r) * B + t;
-            if (g.accumulate) sum += half_bits_to_float(y[o]);
-            y[o] = float_to_half_bits(sum);
-        }
-    }
-}
-
 // ---------------------------------------------------------------------------------------------- up to sixteen activation columns on the matrix cores
 // y[M][B] = (D + S) x[N][B] for 1 <= B <= 16 as a product of 16 x 16 tiles (v_mfma_f32_16x16x16_f16).  The
 // instruction multiplies A (16 rows x 16 k) by B (16 k x 16 columns): lane l supplies A[l % 16][4 (l / 16) + e]
@@ -976,8 +768,8 @@ __device__ __forceinline__ void b16_sparse_finish(const uint16_t* __restrict__ x
     }
 }
 
-// B4 > 0: the batch is exactly 4 B4 columns (4, 8, 12 or 16) and the activations take the fast path below;
-// B4 == 0: any batch up to 16, activations staged as they lie in memory.
+// B4 = 1..4: the batch is exactly 4 B4 columns (4, 8, 12 or 16); B4 = 5: exactly 2 columns -- the activations take the
+// fast paths below;  B4 == 0: any batch up to 16, activations staged as they lie in memory.
 template <int BITS, int RG, int B4>
 __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
     constexpr int R = 16 * RG, K = 1 << BITS;
@@ -1041,7 +833,7 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
     constexpr int kEntryBytes = 4 * TableShape<BITS>::kEntryDwords;   // 4, or 8 for b = 2
     constexpr int kStrideLog2 = (RG == 2 ? 5 : 4) + (kEntryBytes == 8 ? 3 : 2);   // log2(R * kEntryBytes): bytes from one entry to the next
     const u32 tab0 = (u32)r * kEntryBytes;                           // the lane's row of row group 0; the tables start at LDS address 0
-    constexpr int BT = 4 * B4, kPitch = 256 + 16;                    // fast path: columns, bytes of one column's 64 row pairs (+ bank shift)
+    constexpr int BT = B4 == 5 ? 2 : 4 * B4, kPitch = 256 + 16;      // fast path: columns, bytes of one column's 64 row pairs (+ bank shift)
     constexpr u32 kPitchQ = 400;                                     // plane pitch of the 8- and 16-column paths: 64 row pairs + up to 24 dwords of rotation
     auto load_xblock = [&](int t, u32 (&v)[16]) {
         if constexpr (B4 == 4 || B4 == 2) {
@@ -1055,11 +847,16 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
             }
         } else if constexpr (B4 > 0) {
             // lane l fetches rows 2 l and 2 l + 1 of the window: 4 BT contiguous bytes
-            const u32x4* src = reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(x + (size_t)t * kWinCols * BT) + (u32)lane * 4u * BT);
+            const char* src = reinterpret_cast<const char*>(x + (size_t)t * kWinCols * BT) + (u32)lane * 4u * BT;
+            if constexpr (BT == 2) {
+                const u32x2 v2 = *reinterpret_cast<const u32x2*>(src);
+                v[0] = v2.x; v[1] = v2.y;
+            } else {
 #pragma unroll
-            for (int i = 0; i < B4; ++i) {
-                const u32x4 v4 = src[i];
-                v[4 * i] = v4.x; v[4 * i + 1] = v4.y; v[4 * i + 2] = v4.z; v[4 * i + 3] = v4.w;
+                for (int i = 0; i < BT / 4; ++i) {
+                    const u32x4 v4 = reinterpret_cast<const u32x4*>(src)[i];
+                    v[4 * i] = v4.x; v[4 * i + 1] = v4.y; v[4 * i + 2] = v4.z; v[4 * i + 3] = v4.w;
+                }
             }
         } else {
             const char* src = reinterpret_cast<const char*>(x + (size_t)t * kWinCols * B);   // uniform
@@ -1420,24 +1217,6 @@ static hipError_t launch_matvec_t(const MatvecArgs& g, hipStream_t s) {
     }
 }
 
-// windows of two or four activation columns with a dense term: the matrix-core kernel.  Sub-slices per wave by the
-// row length; 16 rows per workgroup (the activations a workgroup stages are then shared by twice as many rows:
-// 8192x8192 23.8 against 28.9 us) except for the widest rows, whose 4 sub-slices leave no registers for it.
-template <int BITS, int G, int XS>
-static hipError_t launch_matvec_b4_x(const MatvecArgs& g, hipStream_t s) {
-    const int W = (g.N + 512 * XS - 1) / (512 * XS);
-    const int waves = W + (g.nnz > 0 ? 2 : 0);
-    const int grid = (g.M + 4 * G - 1) / (4 * G);
-    hipLaunchKernelGGL((matvec_b4_kernel<BITS, G, XS>), dim3(grid), dim3(waves * kWave), (size_t)W * kXPlanesBytes, s, g);
-    return hipGetLastError();
-}
-template <int BITS>
-static hipError_t launch_matvec_b4(const MatvecArgs& g, hipStream_t s) {
-    if (g.N <= 512 * 14) return launch_matvec_b4_x<BITS, 4, 1>(g, s);
-    if (g.N <= 1024 * 14) return launch_matvec_b4_x<BITS, 4, 2>(g, s);
-    return launch_matvec_b4_x<BITS, 2, 4>(g, s);
-}
-
 // up to 16 columns in one launch: 32 rows per workgroup when that still gives every compute unit a workgroup
 // Measured (8192x8192, 11008x4096, 4096x4096, 22016x8192 at 16 columns): 8 waves per workgroup beat 16 (fused 23.4 / 22.2 /
 // 9.8 us against 24.3 / 27.6 / 11.0) and 4 (the sparse term then has too few waves); 32 rows per workgroup beat 16 from
@@ -1461,8 +1240,10 @@ static hipError_t launch_matvec_b16_r(const MatvecArgs& g, hipStream_t s) {
 }
 template <int BITS, int RG>
 static hipError_t launch_matvec_b16_b(const MatvecArgs& g, hipStream_t s) {
-    // batches of exactly 4, 8, 12 or 16 columns: rows of x are whole 8-byte units and take the fast activation path
+    // batches of exactly 2, 4, 8, 12 or 16 columns: pairs of rows of x are whole 8- or 16-byte units and take the fast
+    // activation paths
     switch (g.B) {
+        case 2: return launch_matvec_b16_r<BITS, RG, 5>(g, s);
         case 4: return launch_matvec_b16_r<BITS, RG, 1>(g, s);
         case 8: return launch_matvec_b16_r<BITS, RG, 2>(g, s);
         case 12: return launch_matvec_b16_r<BITS, RG, 3>(g, s);
@@ -1477,15 +1258,16 @@ static hipError_t launch_matvec_b16(const MatvecArgs& g, hipStream_t s) {
 
 template <int BITS>
 static hipError_t launch_matvec_b(const MatvecArgs& g0, hipStream_t s) {
-    // 3 or more columns: one launch of the 16-column kernel, with or without a dense term (at 4 columns 8192x8192 fused
-    // 20.4 against 22.3 us for the 4-column kernel, 4096x4096 8.0 against 9.5); two columns stay with the 4-column kernel
-    if (g0.mfma_batch && g0.B >= 3) {
+    // Two or more columns: one launch of the 16-column kernel (8192x8192 fused at 2 / 4 columns: 19.0 / 20.4 us against 25.1 /
+    // 22.3 us for a kernel built on the 4x4x4 matrix instruction, which this one replaced); without a dense term from three
+    // columns on (two columns: 10.7 us against 7.3 us for the vector-ALU kernel below).
+    if (g0.mfma_batch && (g0.B >= 3 || (g0.B == 2 && g0.qidx))) {
         MatvecArgs g = g0;
         g.bt0 = 0; g.bn = g0.B;
         return launch_matvec_b16<BITS>(g, s);
     }
-    // Everything else -- one column, two columns, calls without a dense term, and calls under an explicit
-    // rows-per-workgroup request -- goes in windows: 4 (or 2) columns per launch when the batch is even (their
+    // Everything else -- one column, two columns without a dense term, and calls under an explicit rows-per-workgroup
+    // request -- goes to the vector-ALU kernel in windows: 4 (or 2) columns per launch when the batch is even (their
     // activations must fit in registers) and one column per launch when it is odd (rows of x are then not dword
     // aligned).  B = 1, 2 and 4 are single launches.
     const int step = g0.B == 1 ? 1 : ((g0.B & 1) ? 1 : 4);
@@ -1494,7 +1276,6 @@ static hipError_t launch_matvec_b(const MatvecArgs& g0, hipStream_t s) {
         g.bt0 = t0; g.bn = min(step, g0.B - t0);
         hipError_t e;
         if (g.bn == 1) e = launch_matvec_t<BITS, 1>(g, s);
-        else if (g.qidx && g.mfma_batch) e = launch_matvec_b4<BITS>(g, s);       // windows of 2 or 4 columns
         else if (g.bn == 2) e = launch_matvec_t<BITS, 2>(g, s);
         else e = launch_matvec_t<BITS, 4>(g, s);
         if (e != hipSuccess) return e;
