@@ -95,9 +95,9 @@ def test_small_layers_all_entry_points(M, N, bits, frac, skew, B):
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
 def test_every_batch_size(bits):
-    """B = 1 .. 16 on one small layer: the one-column kernel, the 4-column kernel (B = 2) and every activation path of
-    the 16-column kernel (4 / 8 / 12 / 16 columns: vector loads and in-register pairing; any other B: staged as it lies
-    in memory), fused, dense only and accumulating."""
+    """B = 1 .. 16 on one small layer: the one-column kernel and every activation path of the 16-column kernel (2 / 4 /
+    8 / 12 / 16 columns: vector loads and in-register pairing; any other B: staged as it lies in memory), fused, dense
+    only and accumulating."""
     M, N = 45, 384
     for B in range(1, 17):
         print(f"case bits={bits} B={B}", flush=True)
