@@ -120,6 +120,31 @@ def test_wide_batches_with_32_rows_per_workgroup(M, N, bits, B):
     check_y(D.matvec().cpu().numpy().view(np.float16).astype(np.float64), y_ref, a_ref, N, "fused")
 
 
+def test_seeded_random_shapes_and_batches():
+    """24 layers drawn from a fixed seed: rows 1..300 (some beyond 8192 for the 32-row workgroups), widths that are
+    multiples of 128 up to 3072, every bit width and batch size, sparse fractions 0 .. 2 % with and without row skew."""
+    rng = np.random.default_rng(20230613)
+    for case in range(24):
+        bits = int(rng.integers(2, 5))
+        B = int(rng.integers(1, 17))
+        N = 128 * int(rng.integers(1, 25))
+        M = int(rng.integers(1, 301)) if case % 6 else 8192 + int(rng.integers(1, 40))
+        if M > 8192:
+            N = 128 * int(rng.integers(1, 3))
+        frac = float(rng.choice([0.0, 0.0005, 0.0045, 0.02]))
+        skew = [None, (0.1, 0.5), (0.01, 0.3)][int(rng.integers(0, 3))]
+        if skew is not None and M < 100:
+            skew = None
+        print(f"case {case}: M={M} N={N} bits={bits} B={B} frac={frac} skew={skew}", flush=True)
+        L = gen.make_layer(M, N, bits, frac=frac, skew=skew, B=B, seed=9000 + case)
+        D = _dev(L)
+        y_ref, a_ref = oracle.layer_matvec(L)
+        check_y(D.matvec().cpu().numpy().view(np.float16).astype(np.float64), y_ref, a_ref, N, f"fused case {case}")
+        if L.nnz:
+            ys, as_ = oracle.layer_matvec(L, dense=False)
+            check_y(D.csr_spmv().cpu().numpy().view(np.float16).astype(np.float64), ys, as_, N, f"sparse case {case}")
+
+
 def test_results_are_reproducible_run_to_run():
     L = gen.make_layer(512, 4096, 3, frac=0.0045, skew=(0.01, 0.3), seed=5)
     D = _dev(L)
