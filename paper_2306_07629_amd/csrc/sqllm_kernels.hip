@@ -730,20 +730,43 @@ __device__ __forceinline__ void b16_sparse_issue(const MatvecArgs& g, const int 
     }
 }
 
-template <int RG, int NS>
+// QT (B a multiple of 4): the activations of a step are gathered with ONE 8-byte load per lane -- lane e of a quad reads
+// the four columns 4 (n / 4) .. + 3 of the x row of ITS nonzero -- and a 4 x 4 transposition inside the quad (three quad
+// permutes) hands every lane its own column of all four nonzeros; otherwise four 16-bit loads per lane.
+template <int RG, int NS, bool QT>
 __device__ __forceinline__ void b16_sparse_finish(const uint16_t* __restrict__ x, int B, int nb, u32 xmask, int lane, const int (&lo)[RG], const int (&hi)[RG],
                                                   const B16SparseSlots<RG, NS>& S, float4v_t (&acc)[RG]) {
     const int q = lane >> 4;
     const char* xb = reinterpret_cast<const char*>(x);
     u32 xa[NS][2], aa[NS][2];
+    if constexpr (QT) {
+        const u32 cg = 4u * ((u32)nb >> 2);                          // first column of the lane's group of four (0 for absent columns)
+        const bool odd = (lane & 1) != 0, upper = (lane & 2) != 0;
+        const u32 sel = odd ? 0x03020706u : 0x05040100u;
+        u32x2 d[NS];
 #pragma unroll
-    for (int k = 0; k < NS; ++k) {
-        // byte offsets fit 32 bits: N * B * 2 < 2^20
-        const u32 c0 = quad_bcast<0>(S.col[k]), c1 = quad_bcast<1>(S.col[k]), c2 = quad_bcast<2>(S.col[k]), c3 = quad_bcast<3>(S.col[k]);
-        const u32 x0 = *reinterpret_cast<const uint16_t*>(xb + 2u * (c0 * (u32)B + (u32)nb)), x1 = *reinterpret_cast<const uint16_t*>(xb + 2u * (c1 * (u32)B + (u32)nb));
-        const u32 x2 = *reinterpret_cast<const uint16_t*>(xb + 2u * (c2 * (u32)B + (u32)nb)), x3 = *reinterpret_cast<const uint16_t*>(xb + 2u * (c3 * (u32)B + (u32)nb));
-        xa[k][0] = (x0 | (x1 << 16)) & xmask;
-        xa[k][1] = (x2 | (x3 << 16)) & xmask;
+        for (int k = 0; k < NS; ++k) d[k] = *reinterpret_cast<const u32x2*>(xb + 2u * (S.col[k] * (u32)B + cg));   // byte offsets fit 32 bits
+#pragma unroll
+        for (int k = 0; k < NS; ++k) {
+            // rows = the quad's four nonzeros, columns = the group's four batch columns; first the 2 x 2 blocks of halves ...
+            const u32 p0 = (u32)__builtin_amdgcn_mov_dpp((int)d[k].x, 0xB1, 0xF, 0xF, true), p1 = (u32)__builtin_amdgcn_mov_dpp((int)d[k].y, 0xB1, 0xF, 0xF, true);
+            const u32 e0 = __builtin_amdgcn_perm(p0, d[k].x, sel), e1 = __builtin_amdgcn_perm(p1, d[k].y, sel);
+            // ... then the dwords between lanes 2 apart
+            const u32 send = upper ? e0 : e1;
+            const u32 recv = (u32)__builtin_amdgcn_mov_dpp((int)send, 0x4E, 0xF, 0xF, true);
+            xa[k][0] = (upper ? recv : e0) & xmask;
+            xa[k][1] = (upper ? e1 : recv) & xmask;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < NS; ++k) {
+            // byte offsets fit 32 bits: N * B * 2 < 2^20
+            const u32 c0 = quad_bcast<0>(S.col[k]), c1 = quad_bcast<1>(S.col[k]), c2 = quad_bcast<2>(S.col[k]), c3 = quad_bcast<3>(S.col[k]);
+            const u32 x0 = *reinterpret_cast<const uint16_t*>(xb + 2u * (c0 * (u32)B + (u32)nb)), x1 = *reinterpret_cast<const uint16_t*>(xb + 2u * (c1 * (u32)B + (u32)nb));
+            const u32 x2 = *reinterpret_cast<const uint16_t*>(xb + 2u * (c2 * (u32)B + (u32)nb)), x3 = *reinterpret_cast<const uint16_t*>(xb + 2u * (c3 * (u32)B + (u32)nb));
+            xa[k][0] = (x0 | (x1 << 16)) & xmask;
+            xa[k][1] = (x2 | (x3 << 16)) & xmask;
+        }
     }
 #pragma unroll
     for (int k = 0; k < NS; ++k) {
@@ -1027,17 +1050,17 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
             if (total - f0 > 8 * NW) {
                 B16SparseSlots<RG, 12> S;
                 b16_sparse_issue<RG, 12>(g, first, count, total, f0, NW, lane, S);
-                b16_sparse_finish<RG, 12>(x, B, nb, xmask, lane, lo, hi, S, acc);
+                b16_sparse_finish<RG, 12, (B4 >= 1 && B4 <= 4)>(x, B, nb, xmask, lane, lo, hi, S, acc);
                 f0 += 12 * NW;
             } else if (total - f0 > 4 * NW) {
                 B16SparseSlots<RG, 8> S;
                 b16_sparse_issue<RG, 8>(g, first, count, total, f0, NW, lane, S);
-                b16_sparse_finish<RG, 8>(x, B, nb, xmask, lane, lo, hi, S, acc);
+                b16_sparse_finish<RG, 8, (B4 >= 1 && B4 <= 4)>(x, B, nb, xmask, lane, lo, hi, S, acc);
                 f0 += 8 * NW;
             } else {
                 B16SparseSlots<RG, 4> S;
                 b16_sparse_issue<RG, 4>(g, first, count, total, f0, NW, lane, S);
-                b16_sparse_finish<RG, 4>(x, B, nb, xmask, lane, lo, hi, S, acc);
+                b16_sparse_finish<RG, 4, (B4 >= 1 && B4 <= 4)>(x, B, nb, xmask, lane, lo, hi, S, acc);
                 f0 += 4 * NW;
             }
         }
