@@ -187,27 +187,38 @@ __device__ __forceinline__ u64 wave_sum_all(u64 v) {
     return v;
 }
 
-// Bitonic steps with compare-exchange distances below 16 on the aligned block of 16 words blk, in registers.
-// FULL: the whole networks k = 2, 4, 8, 16 (start of the sort);  otherwise the steps j = 8, 4, 2, 1 of network k_net >= 32,
-// whose direction is the same for the whole block.
+// The sort is a bitonic network in its all-ascending form: the merge of size k first compares word i of the lower half
+// with its MIRROR image k - 1 - i in the upper half, then runs the usual half-cleaners of distance k/4, k/8, ... 1.  Every
+// comparator puts the smaller word at the lower index, so words past the end of the row, thought of as +infinity, never
+// move and comparators reaching past the end are simply skipped: the cost follows N, not the next power of two.
+// Steps with distances below 16 stay inside aligned blocks of 16 words; a thread runs them in registers:
+// FULL: the whole merges k = 2, 4, 8, 16 (start of the sort);  otherwise the half-cleaners 8, 4, 2, 1 of a later merge.
 template <bool FULL>
-__device__ __forceinline__ void sort_block_steps(u32* __restrict__ A, int blk, int k_net) {
+__device__ __forceinline__ void sort_block_steps(u32* __restrict__ A, int blk) {
     u32 v[16];
     u32x4* src = reinterpret_cast<u32x4*>(A + 16 * blk);
 #pragma unroll
     for (int i = 0; i < 4; ++i) { const u32x4 t4 = src[i]; v[4 * i] = t4.x; v[4 * i + 1] = t4.y; v[4 * i + 2] = t4.z; v[4 * i + 3] = t4.w; }
-    const bool blk_asc = ((16 * blk) & k_net) == 0;                  // FULL: k_net = 16, the direction of network 16
+    auto cx = [&](int a, int b) { const u32 lo = min(v[a], v[b]), hi = max(v[a], v[b]); v[a] = lo; v[b] = hi; };
+    if constexpr (FULL) {
 #pragma unroll
-    for (int k = FULL ? 2 : 16; k <= 16; k <<= 1) {
+        for (int k = 2; k <= 16; k <<= 1) {
 #pragma unroll
-        for (int j = k >> 1; j > 0; j >>= 1) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int a = 2 * i - (i & (j - 1)), b = a + j;
-                const bool asc = (FULL && k < 16) ? (a & k) == 0 : blk_asc;
-                const u32 lo = min(v[a], v[b]), hi = max(v[a], v[b]);
-                v[a] = asc ? lo : hi; v[b] = asc ? hi : lo;
+            for (int i = 0; i < 8; ++i) {                                // mirror step of merge k
+                const int base = (i / (k / 2)) * k, off = i % (k / 2);
+                cx(base + off, base + k - 1 - off);
             }
+#pragma unroll
+            for (int j = k >> 2; j > 0; j >>= 1) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) cx(2 * i - (i & (j - 1)), 2 * i - (i & (j - 1)) + j);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 8; j > 0; j >>= 1) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) cx(2 * i - (i & (j - 1)), 2 * i - (i & (j - 1)) + j);
         }
     }
 #pragma unroll
@@ -292,23 +303,38 @@ __global__ void __launch_bounds__(256) quant_kmeans_kernel(int M, int N, int NP,
     }
     __syncthreads();
 
-    // ---- 3. bitonic sort, ascending.  Compare-exchange distances below 16 stay inside aligned blocks of 16 words: a
-    //         thread takes such a block into registers and runs those steps there (the whole network for k <= 16, the
-    //         last four steps of every later k), so only the distances >= 16 go through LDS one step per barrier:
-    //         45 passes over the row instead of 78 for 4096 words.
-    for (int blk = tid; blk < NP / 16; blk += T) sort_block_steps<true>(A, blk, 16);   // networks k = 2 .. 16
+    // ---- 3. sort, ascending (see sort_block_steps): only the first N words take part; distances >= 16 go through LDS,
+    //         one step per barrier
+    for (int blk = tid; blk < N / 16; blk += T) sort_block_steps<true>(A, blk);       // merges k = 2 .. 16
     __syncthreads();
-    for (int k = 32; k <= NP; k <<= 1) {
-        for (int j = k >> 1; j >= 16; j >>= 1) {
-            for (int i = tid; i < NP / 2; i += T) {
-                const int a = 2 * i - (i & (j - 1)), b = a + j;
-                const u32 va = A[a], vb = A[b];
-                const bool asc = (a & k) == 0;
-                if ((va > vb) == asc) { A[a] = vb; A[b] = va; }
+    // a thread takes kSortBatch comparators of a step at a time: all loads, then all exchanges (the comparators of a step
+    // are independent, and one at a time each is a full LDS round trip with nothing to overlap it)
+    constexpr int kSortBatch = 4;
+    auto lds_step = [&](auto pair_of) {
+        for (int i0 = tid; i0 < NP / 2; i0 += kSortBatch * T) {
+            int a[kSortBatch], b[kSortBatch];
+            u32 va[kSortBatch], vb[kSortBatch];
+            bool live[kSortBatch];
+#pragma unroll
+            for (int u = 0; u < kSortBatch; ++u) {
+                pair_of(i0 + u * T, a[u], b[u]);
+                live[u] = i0 + u * T < NP / 2 && b[u] < N;               // a < b always
+                if (live[u]) { va[u] = A[a[u]]; vb[u] = A[b[u]]; }
             }
-            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kSortBatch; ++u)
+                if (live[u] && va[u] > vb[u]) { A[a[u]] = vb[u]; A[b[u]] = va[u]; }
+            if (a[0] >= N) break;                                        // a grows with i
         }
-        for (int blk = tid; blk < NP / 16; blk += T) sort_block_steps<false>(A, blk, k);   // j = 8, 4, 2, 1 of network k
+        __syncthreads();
+    };
+    for (int k = 32; k <= NP; k <<= 1) {
+        const int hk = k >> 1;
+        // mirror step: word off of the lower half against word k - 1 - off of the upper half of every group of k
+        lds_step([&](int i, int& a, int& b) { const int base = (i / hk) * k, off = i & (hk - 1); a = base + off; b = base + k - 1 - off; });
+        for (int j = k >> 2; j >= 16; j >>= 1)
+            lds_step([&](int i, int& a, int& b) { a = 2 * i - (i & (j - 1)); b = a + j; });
+        for (int blk = tid; blk < N / 16; blk += T) sort_block_steps<false>(A, blk);  // half-cleaners 8, 4, 2, 1
         __syncthreads();
     }
 
