@@ -177,14 +177,28 @@ __global__ void __launch_bounds__(1024) quant_scan_kernel(int M, int* __restrict
     for (int i = b; i < e; ++i) { run += rowptr[i + 1]; rowptr[i + 1] = run; }
 }
 
-// sums over the 64 lanes, valid in every lane
-__device__ __forceinline__ int wave_sum_all(int v) {
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+// Sum of a 32-bit integer over the 64 lanes with DPP moves (no LDS traffic), returned as a uniform value.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ int dpp_add(int v) { return v + __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xF, false); }
+__device__ __forceinline__ int wave_sum_i32(int v) {
+    v = dpp_add<0xB1>(v);            // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);            // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);           // row_half_mirror
+    v = dpp_add<0x140>(v);           // row_mirror: every lane holds the sum of its row of 16
+    v = dpp_add<0x142, 0xA>(v);      // row_bcast:15 into rows 1 and 3
+    v = dpp_add<0x143, 0xC>(v);      // row_bcast:31 into rows 2 and 3: lane 63 holds the total
+    return __builtin_amdgcn_readlane(v, 63);
 }
-__device__ __forceinline__ u64 wave_sum_all(u64 v) {
-    for (int off = 32; off > 0; off >>= 1) v += (u64)__shfl_xor((long long)v, off, 64);
-    return v;
+// The three sums a boundary needs over the lanes' (sensitivity, product) pairs -- sum s, sum of the low words and sum of
+// the high words of the products p = s * w * 2^24 -- from four 32-bit reductions: s < 2^16 and |p| < 2^57, so the 16-bit
+// halves of the low word and the (signed) high word all add up over 64 lanes without overflow.
+__device__ __forceinline__ void wave_sums(u32 sv, i64 p, u64& s0, u64& lo, u64& hi) {
+    const u32 plo = (u32)((u64)p & 0xFFFFFFFFull);
+    const int phi = (int)(p >> 32);
+    const u32 a = (u32)wave_sum_i32((int)(plo & 0xFFFFu)), b = (u32)wave_sum_i32((int)(plo >> 16));
+    s0 = (u64)(u32)wave_sum_i32((int)sv);
+    lo = (u64)a + ((u64)b << 16);
+    hi = (u64)(i64)wave_sum_i32(phi);
 }
 
 // The sort is a bitonic network in its all-ascending form: the merge of size k first compares word i of the lower half
@@ -228,7 +242,7 @@ __device__ __forceinline__ void sort_block_steps(u32* __restrict__ A, int blk) {
 // One block of 256 threads per row.  In one dimension the clusters of Lloyd's method are intervals of the sorted
 // weights, so the row is sorted once and every iteration only moves K - 1 boundaries:
 //   * LDS holds the row's dense weights as (key << 16 | sensitivity), sorted ascending by a bitonic network
-//     (extracted positions and the padding up to a power of two are 0xFFFFFFFF and end up behind the dense ones),
+//     (extracted positions are 0xFFFFFFFF and end up behind the dense ones; the network skips what lies past the row),
 //     and the running sums (sum s, low and high words of sum s w 2^24) in front of every chunk of 64 sorted weights.
 //   * A boundary position p_k = #{ j : fp32(2 w_j) <= fp32(c_k + c_{k+1}) } is found by a 64-way search (every lane
 //     probes one position per round, three rounds cover 2^18 weights); the sums in front of p_k are the chunk's running
@@ -236,15 +250,15 @@ __device__ __forceinline__ void sort_block_steps(u32* __restrict__ A, int blk) {
 //     These are the same decisions and the same exact integer sums as a pass over all weights, hence the same result.
 //   * "No weight changed its cluster" is "no boundary position moved".
 // The final indices and the packed stream are produced from the row as it lies in memory.
-template <int BITS>
-__global__ void __launch_bounds__(256) quant_kmeans_kernel(int M, int N, int NP, int max_iter, const uint16_t* __restrict__ w, const uint16_t* __restrict__ sens,
+template <int BITS, int T>
+__global__ void __launch_bounds__(T) quant_kmeans_kernel(int M, int N, int NP, int max_iter, const uint16_t* __restrict__ w, const uint16_t* __restrict__ sens,
                                                          const u32* __restrict__ ws, const int* __restrict__ rowptr, void* __restrict__ qidx,
                                                          uint16_t* __restrict__ lut, int* __restrict__ cols, uint16_t* __restrict__ vals, int* __restrict__ iters) {
-    constexpr int K = 1 << BITS, T = 256;
+    constexpr int K = 1 << BITS;
     extern __shared__ __align__(16) char smem[];
-    u32* A = reinterpret_cast<u32*>(smem);                           // [NP]
-    const int NC = NP / 64;
-    u64* c0 = reinterpret_cast<u64*>(A + NP);                        // [NC + 1] running sum of s in front of chunk c
+    u32* A = reinterpret_cast<u32*>(smem);                           // [N]; NP (the next power of two) only bounds the sort's merges
+    const int NC = N / 64;
+    u64* c0 = reinterpret_cast<u64*>(A + N);                        // [NC + 1] running sum of s in front of chunk c
     u64* clo = c0 + (NC + 1);                                        // low words of s * w * 2^24
     u64* chi = clo + (NC + 1);                                       // high words (two's complement)
     __shared__ u64 F0[K + 1], Flo[K + 1], Fhi[K + 1];
@@ -257,13 +271,13 @@ __global__ void __launch_bounds__(256) quant_kmeans_kernel(int M, int N, int NP,
     const uint16_t* __restrict__ wrow = w + (size_t)row * N;
     const uint16_t* __restrict__ srow = sens + (size_t)row * N;
 
-    // ---- 1. the row into LDS as sortable words; extracted positions and padding become 0xFFFFFFFF
+    // ---- 1. the row into LDS as sortable words; extracted positions become 0xFFFFFFFF
     {
         const u32x4* wr = reinterpret_cast<const u32x4*>(wrow);
         const u32x4* sr = reinterpret_cast<const u32x4*>(srow);
-        for (int i = tid; i < NP / 8; i += T) {
+        for (int i = tid; i < N / 8; i += T) {
             u32 out[8];
-            if (i < N / 8) {
+            {
                 const u32x4 wv = wr[i], sv = sr[i];
                 const u32 wd[4] = {wv.x, wv.y, wv.z, wv.w}, sd[4] = {sv.x, sv.y, sv.z, sv.w};
 #pragma unroll
@@ -272,9 +286,6 @@ __global__ void __launch_bounds__(256) quant_kmeans_kernel(int M, int N, int NP,
                     out[2 * k] = is_extracted(w0, s0, key_min, key_max, s_thr) ? 0xFFFFFFFFu : (half_key(w0) << 16) | s0;
                     out[2 * k + 1] = is_extracted(w1, s1, key_min, key_max, s_thr) ? 0xFFFFFFFFu : (half_key(w1) << 16) | s1;
                 }
-            } else {
-#pragma unroll
-                for (int k = 0; k < 8; ++k) out[k] = 0xFFFFFFFFu;
             }
             reinterpret_cast<u32x4*>(A)[2 * i] = u32x4{out[0], out[1], out[2], out[3]};
             reinterpret_cast<u32x4*>(A)[2 * i + 1] = u32x4{out[4], out[5], out[6], out[7]};
@@ -342,14 +353,15 @@ __global__ void __launch_bounds__(256) quant_kmeans_kernel(int M, int N, int NP,
     const int nchunks = (n_dense + 63) / 64;
     for (int c = wave; c < nchunks; c += T / 64) {
         const int j = c * 64 + lane;
-        u64 s0 = 0, lo = 0, hi = 0;
+        u32 sv = 0;
+        i64 p = 0;
         if (j < n_dense) {
             const u32 v = A[j];
-            s0 = v & 0xFFFFu;
-            const i64 p = (i64)s0 * half_to_fixed(key_half(v >> 16));
-            lo = (u64)p & 0xFFFFFFFFull; hi = (u64)(p >> 32);
+            sv = v & 0xFFFFu;
+            p = (i64)sv * half_to_fixed(key_half(v >> 16));
         }
-        s0 = wave_sum_all(s0); lo = wave_sum_all(lo); hi = wave_sum_all(hi);
+        u64 s0, lo, hi;
+        wave_sums(sv, p, s0, lo, hi);
         if (lane == 0) { c0[c + 1] = s0; clo[c + 1] = lo; chi[c + 1] = hi; }
     }
     __syncthreads();
@@ -389,14 +401,15 @@ __global__ void __launch_bounds__(256) quant_kmeans_kernel(int M, int N, int NP,
                 }
                 const int p = lo;
                 const int c = p >> 6, inside = p & 63;
-                u64 s0 = 0, l = 0, h = 0;
+                u32 sv = 0;
+                i64 pr = 0;
                 if (lane < inside) {
                     const u32 v = A[c * 64 + lane];
-                    s0 = v & 0xFFFFu;
-                    const i64 pr = (i64)s0 * half_to_fixed(key_half(v >> 16));
-                    l = (u64)pr & 0xFFFFFFFFull; h = (u64)(pr >> 32);
+                    sv = v & 0xFFFFu;
+                    pr = (i64)sv * half_to_fixed(key_half(v >> 16));
                 }
-                s0 = wave_sum_all(s0); l = wave_sum_all(l); h = wave_sum_all(h);
+                u64 s0, l, h;
+                wave_sums(sv, pr, s0, l, h);
                 if (lane == 0) {
                     pos[k + 1] = p; F0[k + 1] = c0[c] + s0; Flo[k + 1] = clo[c] + l; Fhi[k + 1] = chi[c] + h;
                     if (p != prevpos[k + 1]) flag = 1;
@@ -489,27 +502,26 @@ hipError_t launch_quantize(const QuantArgs& a, hipStream_t s) {
     hipLaunchKernelGGL(quant_scan_kernel, dim3(1), dim3(1024), 0, s, a.M, a.rowptr);
     int NP = 128;
     while (NP < a.N) NP <<= 1;
-    const size_t lds = (size_t)NP * 4 + (size_t)(NP / 64 + 1) * 24;
-    hipError_t e = hipSuccess;
-    if (a.bits == 2) {
-        static bool enabled = false;
-        if (!enabled) { e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_kmeans_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024); enabled = true; }
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((quant_kmeans_kernel<2>), dim3(a.M), dim3(256), lds, s, a.M, a.N, NP, a.max_iter, static_cast<const uint16_t*>(a.w), static_cast<const uint16_t*>(a.sens),
-                           ws, a.rowptr, a.qidx, static_cast<uint16_t*>(a.lut), a.cols, static_cast<uint16_t*>(a.vals), a.iters);
-    } else if (a.bits == 3) {
-        static bool enabled = false;
-        if (!enabled) { e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_kmeans_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024); enabled = true; }
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((quant_kmeans_kernel<3>), dim3(a.M), dim3(256), lds, s, a.M, a.N, NP, a.max_iter, static_cast<const uint16_t*>(a.w), static_cast<const uint16_t*>(a.sens),
-                           ws, a.rowptr, a.qidx, static_cast<uint16_t*>(a.lut), a.cols, static_cast<uint16_t*>(a.vals), a.iters);
-    } else {
-        static bool enabled = false;
-        if (!enabled) { e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_kmeans_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024); enabled = true; }
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((quant_kmeans_kernel<4>), dim3(a.M), dim3(256), lds, s, a.M, a.N, NP, a.max_iter, static_cast<const uint16_t*>(a.w), static_cast<const uint16_t*>(a.sens),
-                           ws, a.rowptr, a.qidx, static_cast<uint16_t*>(a.lut), a.cols, static_cast<uint16_t*>(a.vals), a.iters);
+    const size_t lds = (size_t)a.N * 4 + (size_t)(a.N / 64 + 1) * 24;
+    // Threads per row by the row's LDS footprint (the kernel is bound by LDS and barrier latency, so it wants 16 or more
+    // waves per compute unit): 256 up to 4096 weights (eight workgroups per unit), 512 up to 16384 (2-4 workgroups), 1024
+    // beyond (one).  Measured: 4096x11008 2.24 -> 1.79 ms and 8192x8192 2.30 -> 2.08 ms with 512 instead of 256 threads,
+    // 8192x22016 9.95 -> 8.39 ms with 1024 instead of 512; 4096x4096 0.61 -> 0.67 ms with 512 (so 256 there).
+    auto go = [](auto kernel) { return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024); };
+    const int threads = a.N > 16384 ? 1024 : (a.N > 4096 ? 512 : 256);
+#define SQ_LAUNCH_KMEANS(B_, T_)                                                                                                     \
+    {                                                                                                                                \
+        static bool enabled = false;                                                                                                 \
+        if (!enabled) { const hipError_t e = go(&quant_kmeans_kernel<B_, T_>); if (e != hipSuccess) return e; enabled = true; }      \
+        hipLaunchKernelGGL((quant_kmeans_kernel<B_, T_>), dim3(a.M), dim3(T_), lds, s, a.M, a.N, NP, a.max_iter,                       \
+                           static_cast<const uint16_t*>(a.w), static_cast<const uint16_t*>(a.sens), ws, a.rowptr, a.qidx,           \
+                           static_cast<uint16_t*>(a.lut), a.cols, static_cast<uint16_t*>(a.vals), a.iters);                         \
     }
+#define SQ_LAUNCH_KMEANS_T(B_)                                                                                                      \
+    { if (threads == 1024) SQ_LAUNCH_KMEANS(B_, 1024) else if (threads == 512) SQ_LAUNCH_KMEANS(B_, 512) else SQ_LAUNCH_KMEANS(B_, 256) }
+    if (a.bits == 2) SQ_LAUNCH_KMEANS_T(2) else if (a.bits == 3) SQ_LAUNCH_KMEANS_T(3) else SQ_LAUNCH_KMEANS_T(4)
+#undef SQ_LAUNCH_KMEANS_T
+#undef SQ_LAUNCH_KMEANS
     return hipGetLastError();
 }
 
