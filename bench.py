@@ -124,7 +124,7 @@ def bench_quantize(args):
         "weights_per_second": M * N / (sec / args.steps), "parity": "bit-exact on the split and on sampled rows",
         "host_wall_s_timed_region": wall,
         "roofline": {"bound": "alu", "achieved": tops, "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": tops / ALU_PEAK_TOPS, "traffic": None,
-                     "kernel": f"sqllm::quant_kmeans_kernel<{bits}> (87-96 % of the call; the 7 split kernels are timed with it)",
+                     "kernel": f"sqllm::quant_kmeans_kernel<{bits},*> (80-90 % of the call; the 7 split kernels are timed with it)",
                      "note": "operations of the plain method (a pass over all weights per update); the kernel sorts the row and moves boundaries instead",
                      "algorithmic_lane_ops_per_launch": ops},
         "cpu_baseline": cpu,
