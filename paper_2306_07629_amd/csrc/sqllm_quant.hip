@@ -71,27 +71,38 @@ __global__ void __launch_bounds__(256) quant_hist1_kernel(long long units, const
     if (ts) atomicAdd(&ws[kWsHist1S + threadIdx.x], ts);
 }
 
-// bin holding the element of rank r (0-based) in a 256-bin histogram (in LDS), and the rank inside that bin
-__device__ inline void select_bin(const u32* hist, u64 r, u32& bin, u64& residual) {
-    u64 cum = 0;
-    bin = 255; residual = 0;
-    for (u32 b = 0; b < 256; ++b) {
-        const u64 h = hist[b];
-        if (r < cum + h) { bin = b; residual = r - cum; return; }
-        cum += h;
+// Bin holding the element of rank r (0-based) in a 256-bin histogram, and the rank inside that bin; called by all 256
+// threads of the block, thread t owning bin t.  The bin is the one whose running count first exceeds r.
+__device__ inline void select_bin(u32 mine, u64 r, u64* scan /* [256] in LDS */, u32& bin, u64& residual) {
+    const int t = threadIdx.x;
+    scan[t] = mine;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+        const u64 v = t >= off ? scan[t - off] : 0;
+        __syncthreads();
+        scan[t] += v;
+        __syncthreads();
     }
+    const u64 incl = scan[t], excl = incl - mine;
+    __shared__ u32 sel_bin;
+    __shared__ u64 sel_res;
+    if (t == 0) { sel_bin = 255; sel_res = 0; }                      // rank past the end (cannot happen for valid counts)
+    __syncthreads();
+    if (r >= excl && r < incl) { sel_bin = (u32)t; sel_res = r - excl; }
+    __syncthreads();
+    bin = sel_bin; residual = sel_res;
+    __syncthreads();
 }
 
 __global__ void __launch_bounds__(256) quant_select1_kernel(u64 total, u64 n_lo, u64 n_hi, u64 n_sens, u32* ws) {
-    __shared__ u32 h[2][256];
-    h[0][threadIdx.x] = ws[kWsHist1W + threadIdx.x]; h[1][threadIdx.x] = ws[kWsHist1S + threadIdx.x];
-    __syncthreads();
-    if (threadIdx.x >= 3) return;
-    const int t = threadIdx.x;
-    const u64 rank = t == 0 ? n_lo : (t == 1 ? total - 1 - n_hi : total - 1 - n_sens);
-    u32 bin; u64 res;
-    select_bin(h[t < 2 ? 0 : 1], rank, bin, res);
-    ws[kWsSel + 4 * t] = bin; ws[kWsSel + 4 * t + 1] = (u32)res; ws[kWsSel + 4 * t + 2] = (u32)(res >> 32);
+    __shared__ u64 scan[256];
+    const u32 hw = ws[kWsHist1W + threadIdx.x], hs = ws[kWsHist1S + threadIdx.x];
+    for (int t = 0; t < 3; ++t) {
+        const u64 rank = t == 0 ? n_lo : (t == 1 ? total - 1 - n_hi : total - 1 - n_sens);
+        u32 bin; u64 res;
+        select_bin(t < 2 ? hw : hs, rank, scan, bin, res);
+        if (threadIdx.x == 0) { ws[kWsSel + 4 * t] = bin; ws[kWsSel + 4 * t + 1] = (u32)res; ws[kWsSel + 4 * t + 2] = (u32)(res >> 32); }
+    }
 }
 
 // pass 2: histograms of the low bytes inside the three selected bins
@@ -121,16 +132,13 @@ __global__ void __launch_bounds__(256) quant_hist2_kernel(long long units, const
 }
 
 __global__ void __launch_bounds__(256) quant_select2_kernel(u32* ws) {
-    __shared__ u32 h[3][256];
-#pragma unroll
-    for (int t = 0; t < 3; ++t) h[t][threadIdx.x] = ws[kWsHist2 + 256 * t + threadIdx.x];
-    __syncthreads();
-    if (threadIdx.x >= 3) return;
-    const int t = threadIdx.x;
-    const u64 r = (u64)ws[kWsSel + 4 * t + 1] | ((u64)ws[kWsSel + 4 * t + 2] << 32);
-    u32 lo; u64 res;
-    select_bin(h[t], r, lo, res);
-    ws[kWsThr + t] = (ws[kWsSel + 4 * t] << 8) | lo;
+    __shared__ u64 scan[256];
+    for (int t = 0; t < 3; ++t) {
+        const u64 r = (u64)ws[kWsSel + 4 * t + 1] | ((u64)ws[kWsSel + 4 * t + 2] << 32);
+        u32 lo; u64 res;
+        select_bin(ws[kWsHist2 + 256 * t + threadIdx.x], r, scan, lo, res);
+        if (threadIdx.x == 0) ws[kWsThr + t] = (ws[kWsSel + 4 * t] << 8) | lo;
+    }
 }
 
 __device__ __forceinline__ bool is_extracted(u32 wbits, u32 sv, u32 key_min, u32 key_max, u32 s_thr) {
