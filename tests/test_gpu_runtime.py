@@ -14,12 +14,13 @@ def _f64(t):
     return t.cpu().numpy().view(np.float16).astype(np.float64)
 
 
-def test_graph_replays_match_the_eager_result():
+@pytest.mark.parametrize("B", [1, 16, 7])
+def test_graph_replays_match_the_eager_result(B):
     """the benchmark replays a captured graph: every replay must give the eager result (no memset nodes, no
-    host-side state baked into the capture)"""
+    host-side state baked into the capture); one column, and the matrix-core kernel with both activation paths"""
     import torch
     import paper_2306_07629_amd as sq
-    L = gen.make_layer(1030, 4096, 3, frac=0.0045, skew=(0.1, 0.5), seed=31)
+    L = gen.make_layer(1030, 4096, 3, frac=0.0045, skew=(0.1, 0.5), B=B, seed=31)
     D = sq.DeviceLayer(L)
     eager = D.matvec().clone()
     torch.cuda.synchronize()
