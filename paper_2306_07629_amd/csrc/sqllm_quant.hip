@@ -73,7 +73,7 @@ __global__ void __launch_bounds__(256) quant_hist1_kernel(long long units, const
 
 // Bin holding the element of rank r (0-based) in a 256-bin histogram, and the rank inside that bin; called by all 256
 // threads of the block, thread t owning bin t.  The bin is the one whose running count first exceeds r.
-__device__ inline void select_bin(u32 mine, u64 r, u64* scan /* [256] in LDS */, u32& bin, u64& residual) {
+__device__ __forceinline__ void select_bin(u32 mine, u64 r, u64* scan /* [256] in LDS */, u32& bin, u64& residual) {
     const int t = threadIdx.x;
     scan[t] = mine;
     __syncthreads();
