@@ -209,6 +209,9 @@ __device__ __forceinline__ void wave_sums(u32 sv, i64 p, u64& s0, u64& lo, u64& 
     hi = (u64)(i64)wave_sum_i32(phi);
 }
 
+__device__ __forceinline__ u32 umin(u32 a, u32 b) { return a < b ? a : b; }
+__device__ __forceinline__ u32 umax(u32 a, u32 b) { return a < b ? b : a; }
+
 // The sort is a bitonic network in its all-ascending form: the merge of size k first compares word i of the lower half
 // with its MIRROR image k - 1 - i in the upper half, then runs the usual half-cleaners of distance k/4, k/8, ... 1.  Every
 // comparator puts the smaller word at the lower index, so words past the end of the row, thought of as +infinity, never
@@ -221,7 +224,7 @@ __device__ __forceinline__ void sort_block_steps(u32* __restrict__ A, int blk) {
     u32x4* src = reinterpret_cast<u32x4*>(A + 16 * blk);
 #pragma unroll
     for (int i = 0; i < 4; ++i) { const u32x4 t4 = src[i]; v[4 * i] = t4.x; v[4 * i + 1] = t4.y; v[4 * i + 2] = t4.z; v[4 * i + 3] = t4.w; }
-    auto cx = [&](int a, int b) { const u32 lo = min(v[a], v[b]), hi = max(v[a], v[b]); v[a] = lo; v[b] = hi; };
+    auto cx = [&](int a, int b) { const u32 lo = umin(v[a], v[b]), hi = umax(v[a], v[b]); v[a] = lo; v[b] = hi; };
     if constexpr (FULL) {
 #pragma unroll
         for (int k = 2; k <= 16; k <<= 1) {
@@ -326,33 +329,44 @@ __global__ void __launch_bounds__(T) quant_kmeans_kernel(int M, int N, int NP, i
     //         one step per barrier
     for (int blk = tid; blk < N / 16; blk += T) sort_block_steps<true>(A, blk);       // merges k = 2 .. 16
     __syncthreads();
-    // a thread takes kSortBatch comparators of a step at a time: all loads, then all exchanges (the comparators of a step
-    // are independent, and one at a time each is a full LDS round trip with nothing to overlap it)
-    constexpr int kSortBatch = 4;
-    auto lds_step = [&](auto pair_of) {
-        for (int i0 = tid; i0 < NP / 2; i0 += kSortBatch * T) {
+    // Steps with distances >= 16 through LDS.  A thread takes four NEIGHBOURING comparators at a time -- their lower words
+    // are one 16-byte chunk and so are their upper words (in reverse order for the mirror step) -- and kSortBatch such
+    // quads per round: all loads, then all stores.  Index arithmetic, LDS instructions and round trips are shared by four
+    // comparators, and the 16-byte accesses of neighbouring lanes are conflict-free.
+    constexpr int kSortBatch = 2;
+    auto lds_step = [&](auto quad_of, bool mirror) {
+        for (int g0 = tid; g0 < NP / 8; g0 += kSortBatch * T) {
             int a[kSortBatch], b[kSortBatch];
-            u32 va[kSortBatch], vb[kSortBatch];
+            u32x4 va[kSortBatch], vb[kSortBatch];
             bool live[kSortBatch];
 #pragma unroll
             for (int u = 0; u < kSortBatch; ++u) {
-                pair_of(i0 + u * T, a[u], b[u]);
-                live[u] = i0 + u * T < NP / 2 && b[u] < N;               // a < b always
-                if (live[u]) { va[u] = A[a[u]]; vb[u] = A[b[u]]; }
+                quad_of(4 * (g0 + u * T), a[u], b[u]);                   // first words of the two chunks (multiples of 4)
+                live[u] = g0 + u * T < NP / 8 && b[u] < N;               // a < b always; N is a multiple of 4
+                if (live[u]) { va[u] = *reinterpret_cast<const u32x4*>(A + a[u]); vb[u] = *reinterpret_cast<const u32x4*>(A + b[u]); }
             }
 #pragma unroll
-            for (int u = 0; u < kSortBatch; ++u)
-                if (live[u] && va[u] > vb[u]) { A[a[u]] = vb[u]; A[b[u]] = va[u]; }
-            if (a[0] >= N) break;                                        // a grows with i
+            for (int u = 0; u < kSortBatch; ++u) {
+                if (live[u]) {
+                    const u32x4 x = va[u];
+                    const u32x4 y = mirror ? u32x4{vb[u].w, vb[u].z, vb[u].y, vb[u].x} : vb[u];
+                    const u32x4 lo = {umin(x.x, y.x), umin(x.y, y.y), umin(x.z, y.z), umin(x.w, y.w)};
+                    const u32x4 hi = {umax(x.x, y.x), umax(x.y, y.y), umax(x.z, y.z), umax(x.w, y.w)};
+                    *reinterpret_cast<u32x4*>(A + a[u]) = lo;
+                    *reinterpret_cast<u32x4*>(A + b[u]) = mirror ? u32x4{hi.w, hi.z, hi.y, hi.x} : hi;
+                }
+            }
+            if (a[0] >= N) break;                                        // a grows with the quad index
         }
         __syncthreads();
     };
     for (int k = 32; k <= NP; k <<= 1) {
         const int hk = k >> 1;
-        // mirror step: word off of the lower half against word k - 1 - off of the upper half of every group of k
-        lds_step([&](int i, int& a, int& b) { const int base = (i / hk) * k, off = i & (hk - 1); a = base + off; b = base + k - 1 - off; });
+        // mirror step: word off of the lower half against word k - 1 - off of the upper half of every group of k; the four
+        // partners of the words off .. off + 3 are the chunk that starts at k - 4 - off, read backwards
+        lds_step([&](int i, int& a, int& b) { const int base = (i / hk) * k, off = i & (hk - 1); a = base + off; b = base + k - 4 - off; }, true);
         for (int j = k >> 2; j >= 16; j >>= 1)
-            lds_step([&](int i, int& a, int& b) { a = 2 * i - (i & (j - 1)); b = a + j; });
+            lds_step([&](int i, int& a, int& b) { a = 2 * i - (i & (j - 1)); b = a + j; }, false);
         for (int blk = tid; blk < N / 16; blk += T) sort_block_steps<false>(A, blk);  // half-cleaners 8, 4, 2, 1
         __syncthreads();
     }
