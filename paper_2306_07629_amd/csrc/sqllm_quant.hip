@@ -387,10 +387,21 @@ __global__ void __launch_bounds__(T) quant_kmeans_kernel(int M, int N, int NP, i
         if (lane == 0) { c0[c + 1] = s0; clo[c + 1] = lo; chi[c + 1] = hi; }
     }
     __syncthreads();
-    if (tid == 0) {
-        u64 r0 = 0, rl = 0, rh = 0;
-        c0[0] = 0; clo[0] = 0; chi[0] = 0;
-        for (int c = 1; c <= nchunks; ++c) { r0 += c0[c]; rl += clo[c]; rh += chi[c]; c0[c] = r0; clo[c] = rl; chi[c] = rh; }
+    if (wave == 0) {
+        // running sums over the chunks: every lane of wave 0 takes a run of consecutive chunks, the runs are chained with
+        // a prefix sum across the lanes
+        const int per = (nchunks + 63) / 64;
+        const int cb = min(1 + lane * per, nchunks + 1), ce = min(cb + per, nchunks + 1);
+        u64 t0 = 0, tl = 0, th = 0;
+        for (int c = cb; c < ce; ++c) { t0 += c0[c]; tl += clo[c]; th += chi[c]; }
+        u64 p0 = t0, pl = tl, ph = th;
+        for (int off = 1; off < 64; off <<= 1) {
+            const u64 u0 = (u64)__shfl_up((long long)p0, off, 64), ul = (u64)__shfl_up((long long)pl, off, 64), uh = (u64)__shfl_up((long long)ph, off, 64);
+            if (lane >= off) { p0 += u0; pl += ul; ph += uh; }
+        }
+        u64 r0 = p0 - t0, rl = pl - tl, rh = ph - th;                    // sums in front of the lane's run
+        for (int c = cb; c < ce; ++c) { r0 += c0[c]; rl += clo[c]; rh += chi[c]; c0[c] = r0; clo[c] = rl; chi[c] = rh; }
+        if (lane == 0) { c0[0] = 0; clo[0] = 0; chi[0] = 0; }
     }
     // ---- 5. equal-count start
     if (tid < K) {
