@@ -87,7 +87,7 @@ def _frac(h):
     return Fraction(float(np.uint16(h).view(np.float16)))
 
 
-@pytest.mark.parametrize("bits,N,B", [(3, 128, 1), (4, 32, 1), (3, 256, 2), (4, 64, 3)])
+@pytest.mark.parametrize("bits,N,B", [(3, 128, 1), (4, 32, 1), (3, 256, 2), (4, 64, 3), (2, 128, 5), (3, 128, 16)])
 def test_bruteforce_exact_rationals(bits, N, B):
     """everything at once on a tiny layer: triple loop in exact rational arithmetic (Sec. 4.2: WX = DX + SX)."""
     M = 4
@@ -117,9 +117,9 @@ def test_bruteforce_exact_rationals(bits, N, B):
 
 
 # ---------------------------------------------------------------- P3: two routes
-@pytest.mark.parametrize("bits,skew", [(3, (0.1, 0.5)), (4, None), (3, (0.01, 0.3))])
-def test_two_oracle_routes_agree(bits, skew):
-    L = gen.make_layer(384, 1024, bits, frac=0.0045, skew=skew, B=2, seed=11 + bits)
+@pytest.mark.parametrize("bits,skew,B", [(3, (0.1, 0.5), 2), (4, None, 2), (3, (0.01, 0.3), 2), (2, (0.1, 0.5), 16), (3, None, 11)])
+def test_two_oracle_routes_agree(bits, skew, B):
+    L = gen.make_layer(384, 1024, bits, frac=0.0045, skew=skew, B=B, seed=11 + bits)
     y, a = oracle.layer_matvec(L)
     y2, a2 = nr.matvec(L.M, L.N, L.bits, L.qidx, L.lut, L.rowptr, L.cols, L.vals, L.x)
     assert np.all(np.abs(y - y2) <= 1e-12 * a2)
