@@ -298,6 +298,16 @@ def parse():
     return ap.parse_args()
 
 
+def device_info(torch):
+    """what the runtime reports about the GPU the figures come from (clocks cannot be pinned by an ordinary user)"""
+    p = torch.cuda.get_device_properties(0)
+    info = {"name": p.name, "compute_units": p.multi_processor_count, "memory_gb": round(p.total_memory / 1e9, 1)}
+    for k in ("clock_rate", "memory_clock_rate", "gcnArchName", "L2_cache_size"):
+        if hasattr(p, k):
+            info[k] = getattr(p, k)
+    return info
+
+
 def time_steps(torch, fn, steps, warmup, use_graph=True):
     """W untimed + exactly K timed calls of fn(step), bracketed by device synchronisation, timed with HIP
     events on the launch stream.  With use_graph the K launches are first captured into one HIP graph
@@ -499,6 +509,7 @@ def main():
         "warm_us_per_matvec": sec_warm / launches * 1e6, "warm_effective_gbs": step_bytes * args.steps / sec_warm / 1e9,
         "fp16_gemv_us": {"own_kernel": us_f_own, "torch_mv" if B == 1 else "torch_mm": us_f_torch}, "speedup_vs_fp16": us_f / us_per_matvec,
         "parity_worst_err_over_bound": worst, "launch_mode": "hip_graph_replay" if G else "python_ctypes", "host_wall_s_timed_region": wall_cold,
+        "device": device_info(torch),
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                      "traffic": traffic,
                      "kernel": f"sqllm::matvec_kernel<{bits},1,*>" if B == 1 else f"sqllm::matvec_b16_kernel<{bits},*>",
