@@ -12,7 +12,7 @@
 //   * Dequantisation goes through PAIR TABLES in LDS: for every row of the block the workgroup first builds
 //       b = 3:  64 entries,  entry (a | c << 3) = (lut[a], lut[c]) as two fp16 in one dword   (256 B / row)
 //       b = 4: 256 entries,  entry (a | c << 4) = (lut[a], lut[c])                            (1 KB / row)
-//       b = 2: 256 entries,  entry (a | c << 2 | d << 4 | f << 6) = (lut[a], lut[c], lut[d], lut[f]), 8 bytes  (2 KB / row)
+//       b = 2:  16 entries,  entry (a | c << 2) = (lut[a], lut[c])                            (64 B / row)
 //     so ONE ds_read_b32, addressed by a 6- or 8-bit field of the index stream (two neighbouring indices),
 //     returns a ready-made fp16 pair for v_dot2_f32_f16 (two products, fp32 accumulate).  Measured on MI355X
 //     a wave-wide look-up occupies the LDS for ~4 cycles (64 entries) / ~7 cycles (256 entries, bank
@@ -115,21 +115,17 @@ __device__ __forceinline__ void pair_offsets(const LaneChunk<4>& c, u32 (&a)[16]
 #pragma unroll
     for (int p = 0; p < 16; ++p) a[p] = ((c.q[p >> 2] >> (8 * (p & 3))) & 0xFF) << 2;
 }
-//   b = 2: FOUR indices are one byte of the 64-bit chunk; the table entry is 8 bytes (four fp16), 8 look-ups per lane
+//   b = 2: pair p is nibble p of the 64-bit chunk.
 __device__ __forceinline__ void pair_offsets(const LaneChunk<2>& c, u32 (&a)[16]) {
 #pragma unroll
-    for (int p = 0; p < 8; ++p) a[p] = ((c.q[p >> 2] >> (8 * (p & 3))) & 0xFF) << 3;
-#pragma unroll
-    for (int p = 8; p < 16; ++p) a[p] = 0;
+    for (int p = 0; p < 16; ++p) a[p] = ((c.q[p >> 3] >> (4 * (p & 7))) & 0xF) << 2;
 }
 
 template <int BITS>
 struct TableShape {
-    static constexpr int kGroup = BITS == 2 ? 4 : 2;          // weights returned by one look-up
-    static constexpr int kEntryBits = kGroup * BITS;          // 8, 6 or 8
-    static constexpr int kEntries = 1 << kEntryBits;          // 256, 64 or 256
-    static constexpr int kEntryDwords = kGroup / 2;           // 2, 1 or 1
-    static constexpr int kTableDwords = kEntries * kEntryDwords;   // LDS dwords of one row's table
+    static constexpr int kEntryBits = 2 * BITS;               // a table entry holds the pair of two neighbouring indices: 4, 6 or 8 bits
+    static constexpr int kEntries = 1 << kEntryBits;          // 16, 64 or 256
+    static constexpr int kTableDwords = kEntries;             // LDS dwords of one row's table (one dword = two fp16 per entry)
     static constexpr int kRowBytes = 2 << BITS;               // bytes of one row's fp16 table: 8, 16 or 32
     static constexpr int kRawUnit = kRowBytes < 16 ? kRowBytes : 16;   // bytes of fp16 table one lane fetches
 };
@@ -138,27 +134,16 @@ struct TableShape {
 template <int BITS, int R>
 __device__ __forceinline__ void build_tables(u32* __restrict__ tables, const uint16_t* __restrict__ raw, int lane) {
     constexpr int E = TableShape<BITS>::kEntries, K = 1 << BITS;
-    if constexpr (BITS == 2) {
-        // entry (a | c << 2 | d << 4 | f << 6) = (lut[a], lut[c], lut[d], lut[f]); lane l writes entries l, l + 64, ...
-#pragma unroll
-        for (int u = 0; u < R; ++u) {
-            const u32 v0 = raw[u * K + (lane & 3)], v1 = raw[u * K + ((lane >> 2) & 3)], v2 = raw[u * K + ((lane >> 4) & 3)];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const u32 v3 = raw[u * K + i];
-                *reinterpret_cast<u32x2*>(tables + (u * E + 64 * i + lane) * 2) = u32x2{v0 | (v1 << 16), v2 | (v3 << 16)};
-            }
-        }
-        return;
-    }
 #pragma unroll
     for (int u = 0; u < R; ++u) {
         const u32 lo = raw[u * K + (lane & (K - 1))];           // the same for all entries of this lane
 #pragma unroll
         for (int e0 = 0; e0 < E; e0 += kWave) {
             const int e = e0 + lane;
-            const u32 hi = raw[u * K + (e >> BITS)];
-            tables[u * E + e] = lo | (hi << 16);
+            if (E >= kWave || e < E) {
+                const u32 hi = raw[u * K + (e >> BITS)];
+                tables[u * E + e] = lo | (hi << 16);
+            }
         }
     }
 }
@@ -253,16 +238,8 @@ __device__ __forceinline__ void lookup_chunk(const LaneChunk<BITS>& c, const u32
     u32 a[16];
     pair_offsets(c, a);
     const char* tb = reinterpret_cast<const char*>(table);
-    if constexpr (BITS == 2) {
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
-            const u32x2 v = *reinterpret_cast<const u32x2*>(tb + a[p]);
-            w[2 * p] = v.x; w[2 * p + 1] = v.y;
-        }
-    } else {
-#pragma unroll
-        for (int p = 0; p < 16; ++p) w[p] = *reinterpret_cast<const u32*>(tb + a[p]);
-    }
+    for (int p = 0; p < 16; ++p) w[p] = *reinterpret_cast<const u32*>(tb + a[p]);
 }
 
 // 16 * NB packed dot products (two fp16 products each, fp32 accumulate); two accumulator chains per column
@@ -504,13 +481,10 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
 
     if (wave < W) {
         // ---- dense wave.  Issue order: (wave 0: fp16 tables), activations, first D rows of the index stream.
-        // b = 2: every dense wave fetches and builds the tables of rows wave, wave + W, ... -- one wave building all R
-        // tables (2 KB each) was a serial stretch before the barrier (8192x8192 fused 10.3 -> 9.7 us, 11008x4096 8.4 -> 8.0);
-        // b = 3, 4: wave 0 builds them all (splitting measured 1-2 % slower there).
-        constexpr bool kSplitBuild = BITS == 2;
-        constexpr int LPR = TableShape<BITS>::kRowBytes / kRawUnit;   // lanes fetching one row's fp16 table
-        const int my_rows = kSplitBuild ? (R - wave + W - 1) / W : (wave == 0 ? R : 0);
-        const int bu = kSplitBuild ? wave + (lane / LPR) * W : lane / LPR;   // row of the block this lane fetches a piece of
+        // wave 0 fetches the fp16 tables of the block's rows (LPR lanes per row) and builds their pair tables
+        constexpr int LPR = TableShape<BITS>::kRowBytes / kRawUnit;
+        const int my_rows = wave == 0 ? R : 0;
+        const int bu = lane / LPR;                                    // row of the block this lane fetches a piece of
         u32x4 rawv = {0, 0, 0, 0};
         if (lane < my_rows * LPR) {
             const int row = min(r0 + bu, g.M - 1);
@@ -547,11 +521,7 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            if constexpr (kSplitBuild) {
-                for (int u = wave; u < R; u += W) build_tables<BITS, 1>(tables + u * TD, raw + u * K, lane);
-            } else {
-                build_tables<BITS, R>(tables, raw, lane);
-            }
+            build_tables<BITS, R>(tables, raw, lane);
         }
         __syncthreads();
         // software pipeline: the look-ups of row u + 1 are in flight while the products of row u are formed;
@@ -577,7 +547,7 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
 #pragma unroll
             for (int t = 0; t < NB; ++t) acc[t][u] = a[t];
             if (kInterleave && u + 1 < R) {
-                constexpr int L = 32 / TableShape<BITS>::kGroup;      // look-ups per row slice and lane
+                constexpr int L = 16;                                 // look-ups per row slice and lane
 #pragma unroll
                 for (int p = 0; p < L; ++p) {
                     __builtin_amdgcn_sched_group_barrier(0x2, 2, 0);          // VALU: the offsets of one look-up
@@ -654,9 +624,9 @@ constexpr int kB16StageBytes = 16 * 400;                  // one window of x for
 // Entry-major tables.  Lane l of a 16-lane group decodes its OWN matrix row, so the 32 lanes the LDS serves together
 // read 32 different (row, entry) addresses; with one table after the other every row's entries overlay the same
 // banks and the look-up takes ~7.5 cycles (hardware counters: 58 % of the LDS cycles were bank conflicts).  Here entry
-// e of the block's row rho lives at byte (e R + rho) * kEntryBytes: a row owns one bank (two for b = 2), rows never
+// e of the block's row rho lives at byte (e R + rho) * kEntryBytes: a row owns one bank, rows never
 // collide with each other and only the two lanes of one row can (2 passes per 32 lanes, as with one shared table).
-// LDS addresses of the 16 (b = 2: 8) entries of a lane's chunk: entry index times the entry stride 1 << S, OR the
+// LDS addresses of the 16 entries of a lane's chunk: entry index times the entry stride 1 << S, OR the
 // row's offset `base` < 1 << S (the tables start at LDS address 0: the kernel has no other static or dynamic LDS before them):
 template <int S>
 __device__ __forceinline__ void entry_offsets(const LaneChunk<3>& c, u32 base, u32 (&a)[16]) {
@@ -675,24 +645,14 @@ __device__ __forceinline__ void entry_offsets(const LaneChunk<4>& c, u32 base, u
 template <int S>
 __device__ __forceinline__ void entry_offsets(const LaneChunk<2>& c, u32 base, u32 (&a)[16]) {
 #pragma unroll
-    for (int p = 0; p < 8; ++p) a[p] = (((c.q[p >> 2] >> (8 * (p & 3))) & 0xFFu) << S) | base;
-#pragma unroll
-    for (int p = 8; p < 16; ++p) a[p] = 0;
+    for (int p = 0; p < 16; ++p) a[p] = (((c.q[p >> 3] >> (4 * (p & 7))) & 0xFu) << S) | base;
 }
 template <int BITS, int S>
 __device__ __forceinline__ void lookup_chunk_at(const LaneChunk<BITS>& c, u32 base, u32 (&w)[16]) {
     u32 a[16];
     entry_offsets<S>(c, base, a);
-    if constexpr (BITS == 2) {
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
-            const u32x2 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x2*>(a[p]);
-            w[2 * p] = v.x; w[2 * p + 1] = v.y;
-        }
-    } else {
-#pragma unroll
-        for (int p = 0; p < 16; ++p) w[p] = *reinterpret_cast<const __attribute__((address_space(3))) u32*>(a[p]);
-    }
+    for (int p = 0; p < 16; ++p) w[p] = *reinterpret_cast<const __attribute__((address_space(3))) u32*>(a[p]);
 }
 
 // Sparse term of the 16-column kernel.  Step j covers the nonzeros [16 j, 16 j + 16); the steps overlapping the CSR
@@ -853,8 +813,8 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
 #pragma unroll
     for (int ii = 0; ii < 4; ++ii) eoff[ii] = 4u * (u32)min(64 * ii + lane, qd - 1);
     const u32 stage_lds = (u32)(size_t)stage;                        // LDS byte address of the wave's staging area (uniform)
-    constexpr int kEntryBytes = 4 * TableShape<BITS>::kEntryDwords;   // 4, or 8 for b = 2
-    constexpr int kStrideLog2 = (RG == 2 ? 5 : 4) + (kEntryBytes == 8 ? 3 : 2);   // log2(R * kEntryBytes): bytes from one entry to the next
+    constexpr int kEntryBytes = 4;                                    // one pair of fp16 per entry
+    constexpr int kStrideLog2 = (RG == 2 ? 5 : 4) + 2;               // log2(R * kEntryBytes): bytes from one entry to the next
     const u32 tab0 = (u32)r * kEntryBytes;                           // the lane's row of row group 0; the tables start at LDS address 0
     constexpr int BT = B4 == 5 ? 2 : 4 * B4, kPitch = 256 + 16;      // fast path: columns, bytes of one column's 64 row pairs (+ bank shift)
     constexpr u32 kPitchQ = 400;                                     // plane pitch of the 8- and 16-column paths: 64 row pairs + up to 24 dwords of rotation
@@ -990,13 +950,8 @@ __global__ void __launch_bounds__(1024) matvec_b16_kernel(MatvecArgs g) {
             // consecutive threads write consecutive rows of one entry (conflict-free); see entry_offsets for the layout
             const int rho = o % R, e = o / R;
             const uint16_t* rr = raw + rho * K;
-            if constexpr (BITS == 2) {
-                const u32 v0 = rr[e & 3], v1 = rr[(e >> 2) & 3], v2 = rr[(e >> 4) & 3], v3 = rr[e >> 6];
-                *reinterpret_cast<u32x2*>(tables + 2 * o) = u32x2{v0 | (v1 << 16), v2 | (v3 << 16)};
-            } else {
-                const u32 lo16 = rr[e & (K - 1)], hi16 = rr[e >> BITS];
-                tables[o] = lo16 | (hi16 << 16);
-            }
+            const u32 lo16 = rr[e & (K - 1)], hi16 = rr[e >> BITS];
+            tables[o] = lo16 | (hi16 << 16);
         }
     __syncthreads();
 
