@@ -239,6 +239,34 @@ def bench_decode_step(args):
     }))
 
 
+PROBES = {"probe_lds_valu_overlap"}
+
+
+def bench_probe(args):
+    """the machine probe behind the decode bound: look-ups alone, vector-ALU work alone, both (16 and 8 waves per unit)"""
+    import torch
+    import paper_2306_07629_amd as sq
+    out = torch.zeros(16, dtype=torch.int32, device="cuda")
+    iters = 4000
+    rows = []
+    for waves in (16, 8):
+        for lookups, mads in ((16, 0), (0, 48), (0, 96), (0, 128), (16, 48), (16, 96), (16, 128)):
+            sq.sqllm_probe_lds_valu(lookups, mads, waves, iters, out)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                sq.sqllm_probe_lds_valu(lookups, mads, waves, iters, out)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 3
+            rows.append({"waves_per_cu": waves, "lookups": lookups, "mads": mads, "us": round(us, 1),
+                         "clk_per_wave_iteration_per_cu_at_2.4GHz": round(us * 1e-6 * 2.4e9 / iters / waves, 1)})
+    print(json.dumps({"metric": "clocks per wave-iteration per compute unit: 16 random 64-entry LDS look-ups, integer multiply-adds, both",
+                      "value": None, "unit": "clk", "n_gpus": 1, "steps": 3, "warmup": 1, "higher_is_better": False, "data": "synthetic",
+                      "config": {"workload": args.workload, "iterations_per_wave": iters, "workgroups": 256}, "rows": rows}))
+
+
 def bench_csr_ablation(args):
     import numpy as np
     import torch
@@ -288,7 +316,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", default="llama7b_mlp_pair_3bit", choices=sorted(WORKLOADS) + sorted(QUANT_WORKLOADS) + sorted(CSR_ABLATION) + sorted(DECODE_STEP))
+    ap.add_argument("--workload", default="llama7b_mlp_pair_3bit", choices=sorted(WORKLOADS) + sorted(QUANT_WORKLOADS) + sorted(CSR_ABLATION) + sorted(DECODE_STEP) + sorted(PROBES))
     ap.add_argument("--footprint-gb", type=float, default=1.1, help="bytes of distinct weight copies to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rows-per-wg", type=int, default=0)
@@ -363,6 +391,8 @@ def main():
         if args.steps == 400 and args.warmup == 40:
             args.steps, args.warmup = 200, 20
         return bench_csr_ablation(args)
+    if args.workload in PROBES:
+        return bench_probe(args)
     if args.workload in DECODE_STEP:
         if args.steps == 400 and args.warmup == 40:
             args.steps, args.warmup = 20, 3

@@ -141,6 +141,13 @@ int sqllm_quantize_layer(int M, int N, int bits, int max_iter, const void* w, co
 /* Bytes the method moves for one matvec (indices + tables + CSR arrays + x + y); used for GB/s figures.  */
 long long sqllm_algorithmic_bytes(int M, int N, int bits, long long nnz, int B);
 
+/* Machine probe behind the roofline analysis of the matvec kernels: on every compute unit `waves_per_cu` waves (1..16)
+ * run `iters` iterations of `lookups` (0 or 16) random look-ups in 64-entry LDS tables -- the access pattern of the
+ * 3-bit pair tables -- and `mads` (0, 48, 96 or 128; not both zero) integer multiply-adds.  Timing the call for
+ * (16, 0), (0, m) and (16, m) shows how far look-ups and vector-ALU work of different waves overlap.  `out` is a
+ * device pointer to at least 4 bytes (practically never written).  No relation to any weight data.               */
+int sqllm_probe_lds_valu(int lookups, int mads, int waves_per_cu, int iters, void* out, void* stream);
+
 /* Tuning knob: rows handled by one workgroup of the matvec kernels (0 = library default; other values are
  * rounded up to 2, 4, 8 or 16).  Affects speed only.  Returns the previous value.  Process-wide, not thread-safe. */
 int sqllm_set_rows_per_workgroup(int rows);

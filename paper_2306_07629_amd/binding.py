@@ -17,7 +17,7 @@ STATUS_NAMES = ["SQLLM_OK", "SQLLM_ERR_NULL", "SQLLM_ERR_BITS", "SQLLM_ERR_SHAPE
 EXPORTS = ["sqllm_lut_gemv", "sqllm_csr_spmv", "sqllm_dense_sparse_matvec", "sqllm_csr_spmv_rowwise",
            "sqllm_unpack_indices", "sqllm_dequantize", "sqllm_fp16_gemv", "sqllm_algorithmic_bytes",
            "sqllm_quantize_workspace_bytes", "sqllm_quantize_layer",
-           "sqllm_set_rows_per_workgroup", "sqllm_last_error_string", "sqllm_status_string", "sqllm_version"]
+           "sqllm_probe_lds_valu", "sqllm_set_rows_per_workgroup", "sqllm_last_error_string", "sqllm_status_string", "sqllm_version"]
 
 
 class SqllmError(RuntimeError):
@@ -46,6 +46,7 @@ def lib() -> ctypes.CDLL:
         L.sqllm_quantize_workspace_bytes.argtypes = [i32, i32]
         L.sqllm_quantize_workspace_bytes.restype = i64
         L.sqllm_quantize_layer.argtypes = [i32, i32, i32, i32, vp, vp, i64, i64, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp]
+        L.sqllm_probe_lds_valu.argtypes = [i32, i32, i32, i32, vp, vp]
         L.sqllm_set_rows_per_workgroup.argtypes = [i32]
         L.sqllm_last_error_string.restype = ctypes.c_char_p
         L.sqllm_status_string.argtypes = [i32]
@@ -121,6 +122,10 @@ def sqllm_quantize_layer(M, N, bits, max_iter, w, sens, n_lo, n_hi, n_sens, work
 
 def sqllm_algorithmic_bytes(M, N, bits, nnz, B) -> int:
     return int(lib().sqllm_algorithmic_bytes(M, N, bits, nnz, B))
+
+
+def sqllm_probe_lds_valu(lookups, mads, waves_per_cu, iters, out, stream=None):
+    _check(lib().sqllm_probe_lds_valu(int(lookups), int(mads), int(waves_per_cu), int(iters), _ptr(out), _stream(stream)))
 
 
 def sqllm_set_rows_per_workgroup(rows: int) -> int:

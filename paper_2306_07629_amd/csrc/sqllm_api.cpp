@@ -206,6 +206,18 @@ int sqllm_quantize_layer(int M, int N, int bits, int max_iter, const void* w, co
     return SQLLM_OK;
 }
 
+int sqllm_probe_lds_valu(int lookups, int mads, int waves_per_cu, int iters, void* out, void* stream) {
+    if (!((lookups == 16 && (mads == 0 || mads == 48 || mads == 96 || mads == 128)) || (lookups == 0 && (mads == 48 || mads == 96 || mads == 128))))
+        return fail(SQLLM_ERR_SHAPE, "probe: (lookups, mads) = (%d, %d) is not one of the built combinations", lookups, mads);
+    if (waves_per_cu < 1 || waves_per_cu > 16) return fail(SQLLM_ERR_SHAPE, "probe: waves_per_cu = %d outside 1..16", waves_per_cu);
+    if (iters < 1 || iters > 1000000) return fail(SQLLM_ERR_SHAPE, "probe: iters = %d outside 1..1000000", iters);
+    if (!out) return fail(SQLLM_ERR_NULL, "probe: out must not be NULL");
+    if (misaligned(out, 4)) return fail(SQLLM_ERR_ALIGN, "probe: out must be 4-byte aligned");
+    const hipError_t e = sqllm::launch_probe_lds_valu(lookups, mads, waves_per_cu, iters, out, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "probe launch");
+    return SQLLM_OK;
+}
+
 int sqllm_set_rows_per_workgroup(int rows) {
     const int old = g_rows_per_wg;
     g_rows_per_wg = rows < 0 ? 0 : (rows > 64 ? 64 : rows);

@@ -41,5 +41,6 @@ hipError_t launch_matvec(const MatvecArgs& g, hipStream_t s);
 hipError_t launch_csr_rowwise(const MatvecArgs& g, hipStream_t s);
 hipError_t launch_decode(int M, int N, int bits, const void* qidx, const void* lut, void* idx_out, void* w_out, hipStream_t s);
 hipError_t launch_fp16_gemv(int M, int N, int B, const void* w, const void* x, void* y, hipStream_t s);
+hipError_t launch_probe_lds_valu(int lookups, int mads, int waves_per_cu, int iters, void* out, hipStream_t s);
 
 }  // namespace sqllm

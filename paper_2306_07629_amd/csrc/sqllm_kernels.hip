@@ -1156,6 +1156,47 @@ __global__ void __launch_bounds__(256) fp16_gemv_kernel(int M, int N, int B, con
         }
 }
 
+// ---------------------------------------------------------------------------------------------- machine probe
+// How far do table look-ups (LDS) and vector-ALU work of different waves overlap on a compute unit?  Every wave runs
+// `iters` iterations of NL random look-ups in a private 64-entry table (the access pattern of the 3-bit pair tables) and
+// NV integer multiply-adds in four independent chains.  Timing (NL, 0), (0, NV) and (NL, NV) with 16 waves per compute
+// unit tells whether the two pipelines add up or hide each other; the answer (they mostly add up) is what bounds the
+// decode of the matvec kernels.
+template <int NL, int NV>
+__global__ void __launch_bounds__(1024) probe_lds_valu_kernel(u32* out, int iters, u32 seed) {
+    __shared__ __align__(16) u32 tab[16 * 64];
+    for (int i = threadIdx.x; i < 16 * 64; i += blockDim.x) tab[i] = (u32)i * 7u + seed;
+    __syncthreads();
+    const char* mytab = reinterpret_cast<const char*>(tab) + (threadIdx.x >> 6) * 256;
+    u32 s = (threadIdx.x + blockIdx.x * 1024u) * 2654435761u + seed;
+    auto next = [&]() { s ^= s << 13; s ^= s >> 17; s ^= s << 5; return s; };
+    next(); next();
+    u32 a[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) a[i] = ((next() >> 9) & 63u) * 4u;
+    u32 acc = 0, v0 = s, v1 = s * 3u, v2 = s * 5u, v3 = s * 7u;
+    for (int it = 0; it < iters; ++it) {
+        const u32 m = ((u32)it & 63u) * 4u;                          // uniform: keeps the lanes' indices a random set
+#pragma unroll
+        for (int i = 0; i < NL; ++i) acc ^= *reinterpret_cast<const u32*>(mytab + (a[i] ^ m));
+#pragma unroll
+        for (int i = 0; i < NV / 4; ++i) {
+            v0 = v0 * 0x9E3779B1u + v3; v1 = v1 * 0x85EBCA6Bu + v0; v2 = v2 * 0xC2B2AE35u + v1; v3 = v3 * 0x27D4EB2Fu + v2;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if ((acc ^ v0 ^ v1 ^ v2 ^ v3) == 0x12345u) out[0] = acc;         // keeps the work alive; practically never true
+}
+
+hipError_t launch_probe_lds_valu(int lookups, int mads, int waves_per_cu, int iters, void* out, hipStream_t s) {
+    const dim3 grid(256), block(64 * waves_per_cu);
+    u32* o = static_cast<u32*>(out);
+#define SQ_PROBE(NL_, NV_) if (lookups == NL_ && mads == NV_) { hipLaunchKernelGGL((probe_lds_valu_kernel<NL_, NV_>), grid, block, 0, s, o, iters, 17u); return hipGetLastError(); }
+    SQ_PROBE(16, 0) SQ_PROBE(16, 48) SQ_PROBE(16, 96) SQ_PROBE(16, 128) SQ_PROBE(0, 48) SQ_PROBE(0, 96) SQ_PROBE(0, 128)
+#undef SQ_PROBE
+    return hipErrorInvalidValue;
+}
+
 // ---------------------------------------------------------------------------------------------- launchers
 template <int BITS, int NB, int R, int D>
 static hipError_t launch_matvec_r(const MatvecArgs& g, hipStream_t s) {

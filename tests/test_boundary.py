@@ -90,6 +90,16 @@ def test_debug_and_baseline_argument_errors():
     expect("SQLLM_ERR_BATCH", sq.sqllm_fp16_gemv, 4, 16, 0, A, A, A)
 
 
+def test_probe_argument_errors():
+    f = sq.sqllm_probe_lds_valu
+    expect("SQLLM_ERR_SHAPE", f, 16, 7, 16, 100, A)
+    expect("SQLLM_ERR_SHAPE", f, 0, 0, 16, 100, A)
+    expect("SQLLM_ERR_SHAPE", f, 16, 48, 17, 100, A)
+    expect("SQLLM_ERR_SHAPE", f, 16, 48, 16, 0, A)
+    expect("SQLLM_ERR_NULL", f, 16, 48, 16, 100, None)
+    expect("SQLLM_ERR_ALIGN", f, 16, 48, 16, 100, A + 2)
+
+
 def test_empty_problem_is_ok_without_a_device():
     # M == 0: nothing to do, nothing is enqueued, no HIP call is made
     sq.sqllm_lut_gemv(0, 128, 3, 1, A, A, A, A, stream=0)
