@@ -105,3 +105,15 @@ def test_inputs_at_the_very_end_of_an_allocation():
         y = _f64(D.matvec())
         y_ref, absdot = oracle.layer_matvec(L)
         assert (np.abs(y - y_ref) <= TOL * absdot).all()
+
+
+def test_machine_probe_runs():
+    """the LDS / vector-ALU overlap probe: every built combination launches and finishes"""
+    import torch
+    import paper_2306_07629_amd as sq
+    out = torch.zeros(4, dtype=torch.int32, device="cuda")
+    for lookups, mads in ((16, 0), (0, 48), (16, 48), (16, 128)):
+        sq.sqllm_probe_lds_valu(lookups, mads, 4, 50, out)
+    torch.cuda.synchronize()
+    with pytest.raises(sq.SqllmError):
+        sq.sqllm_probe_lds_valu(16, 5, 4, 50, out)
