@@ -1,14 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the Dense-and-Sparse LUT matvec on one MI355X.
 
-Workload (default): the LLaMA-7B-shaped MLP pair at 3 bits — layers 11008x4096 and 4096x11008, 8 fp16
-centroids per output row, 0.45 % fp16 CSR outliers with row-skewed counts (10 % of the rows hold 50 % of the
-nonzeros), batch 1, synthetic seeded weights (Student-t(4) * 0.02) and N(0,1) activations.
+Workload (default): the LLaMA-65B-shaped MLP pair at 3 bits — layers 22016x8192 and 8192x22016, the largest
+single-GPU configuration of the benchmark list: 8 fp16 centroids per output row, 0.45 % fp16 CSR outliers with
+heavy row skew (1 % of the rows hold 30 % of the nonzeros), batch 1, synthetic seeded weights (Student-t(4) * 0.02)
+and N(0,1) activations.
 
 A "step" is one pass of the hot path over that pair: two calls of sqllm_dense_sparse_matvec, back to back on
 one stream.  To measure HBM and not the 256 MB last-level cache, the steps rotate over enough copies of the
 two layers (at distinct addresses) for the working set to exceed 1 GB.  All inputs are resident in HBM
-before the timed region starts.  Prints ONE JSON line.
+before the timed region starts.  The K steps are captured in one HIP graph that is replayed several times; the
+median replay is the reported time (minimum and maximum are printed beside it).  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -71,7 +73,7 @@ def bench_quantize(args):
     K = 1 << bits
     w = gen.make_weights(M, N, gen.layer_seed(SEED, 6, 0))
     s = gen.make_sens(M, N, gen.layer_seed(SEED, 6, 0))
-    n_lo, n_hi, n_sens = sq.extraction_counts(M, N, of, sf)
+    n_lo, n_hi, n_sens = sq.sqllm_extraction_counts(M, N, of, sf)
     wd = torch.from_numpy(w.view(np.int16)).cuda()
     sd = torch.from_numpy(s.view(np.int16)).cuda()
     q = sq.quantize_layer(wd, sd, bits, n_lo, n_hi, n_sens, max_iter)
@@ -189,7 +191,7 @@ def bench_decode_step(args):
             D.matvec()
 
     G = not args.no_graph
-    sec, wall = time_steps(torch, step, args.steps, args.warmup, G)
+    sec, wall = time_steps(torch, step, args.steps, args.warmup, G, args.replays, tag="cold")
     us_step = sec / args.steps * 1e6
     gbs = step_bytes * args.steps / sec / 1e9
 
@@ -239,34 +241,6 @@ def bench_decode_step(args):
     }))
 
 
-PROBES = {"probe_lds_valu_overlap"}
-
-
-def bench_probe(args):
-    """the machine probe behind the decode bound: look-ups alone, vector-ALU work alone, both (16 and 8 waves per unit)"""
-    import torch
-    import paper_2306_07629_amd as sq
-    out = torch.zeros(16, dtype=torch.int32, device="cuda")
-    iters = 4000
-    rows = []
-    for waves in (16, 8):
-        for lookups, mads in ((16, 0), (0, 48), (0, 96), (0, 128), (16, 48), (16, 96), (16, 128)):
-            sq.sqllm_probe_lds_valu(lookups, mads, waves, iters, out)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(3):
-                sq.sqllm_probe_lds_valu(lookups, mads, waves, iters, out)
-            e1.record()
-            torch.cuda.synchronize()
-            us = e0.elapsed_time(e1) * 1e3 / 3
-            rows.append({"waves_per_cu": waves, "lookups": lookups, "mads": mads, "us": round(us, 1),
-                         "clk_per_wave_iteration_per_cu_at_2.4GHz": round(us * 1e-6 * 2.4e9 / iters / waves, 1)})
-    print(json.dumps({"metric": "clocks per wave-iteration per compute unit: 16 random 64-entry LDS look-ups, integer multiply-adds, both",
-                      "value": None, "unit": "clk", "n_gpus": 1, "steps": 3, "warmup": 1, "higher_is_better": False, "data": "synthetic",
-                      "config": {"workload": args.workload, "iterations_per_wave": iters, "workgroups": 256}, "rows": rows}))
-
-
 def bench_csr_ablation(args):
     import numpy as np
     import torch
@@ -314,15 +288,13 @@ def bench_csr_ablation(args):
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", default="llama7b_mlp_pair_3bit", choices=sorted(WORKLOADS) + sorted(QUANT_WORKLOADS) + sorted(CSR_ABLATION) + sorted(DECODE_STEP) + sorted(PROBES))
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--replays", type=int, default=11, help="timed replays of the captured K steps; the median is reported")
+    ap.add_argument("--workload", default="llama65b_mlp_pair_3bit", choices=sorted(WORKLOADS) + sorted(QUANT_WORKLOADS) + sorted(CSR_ABLATION) + sorted(DECODE_STEP))
     ap.add_argument("--footprint-gb", type=float, default=1.1, help="bytes of distinct weight copies to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--rows-per-wg", type=int, default=0)
     ap.add_argument("--no-graph", action="store_true", help="issue every launch from Python instead of replaying a HIP graph")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain 256 MiB device copy 20 times (reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -336,15 +308,19 @@ def device_info(torch):
     return info
 
 
-def time_steps(torch, fn, steps, warmup, use_graph=True):
+REPLAY_STATS = {}
+
+
+def time_steps(torch, fn, steps, warmup, use_graph=True, replays=11, tag=None):
     """W untimed + exactly K timed calls of fn(step), bracketed by device synchronisation, timed with HIP
     events on the launch stream.  With use_graph the K launches are first captured into one HIP graph
     (still K separate kernel launches, executed in order on one stream) so that the Python/ctypes cost of
-    issuing a launch (about 10 us, more than the kernel itself) is not what is measured."""
+    issuing a launch (about 10 us, more than the kernel itself) is not what is measured; the graph is replayed
+    `replays` times, each replay timed by its own event pair, and the MEDIAN replay is returned (seconds for the
+    K steps) with the host wall time of that many steps.  Minimum and maximum go to REPLAY_STATS[tag]."""
     for s in range(warmup):
         fn(s)
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     if use_graph:
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -356,13 +332,22 @@ def time_steps(torch, fn, steps, warmup, use_graph=True):
             torch.cuda.synchronize()
             graph.replay()                       # untimed first replay (uploads the graph)
             torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            e0.record()
-            graph.replay()
-            e1.record()
-            torch.cuda.synchronize()
-            wall = time.perf_counter() - t0
-        return e0.elapsed_time(e1) * 1e-3, wall
+            secs, walls = [], []
+            for _ in range(max(1, replays)):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                t0 = time.perf_counter()
+                e0.record()
+                graph.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                walls.append(time.perf_counter() - t0)
+                secs.append(e0.elapsed_time(e1) * 1e-3)
+        order = sorted(range(len(secs)), key=lambda i: secs[i])
+        mid = order[len(order) // 2]
+        if tag:
+            REPLAY_STATS[tag] = {"replays": len(secs), "median_ms": secs[mid] * 1e3, "min_ms": min(secs) * 1e3, "max_ms": max(secs) * 1e3}
+        return secs[mid], walls[mid]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
     for s in range(steps):
@@ -370,6 +355,8 @@ def time_steps(torch, fn, steps, warmup, use_graph=True):
     e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    if tag:
+        REPLAY_STATS[tag] = {"replays": 1, "median_ms": e0.elapsed_time(e1), "min_ms": e0.elapsed_time(e1), "max_ms": e0.elapsed_time(e1)}
     return e0.elapsed_time(e1) * 1e-3, wall
 
 
@@ -388,22 +375,18 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
     if args.workload in CSR_ABLATION:
-        if args.steps == 400 and args.warmup == 40:
+        if args.steps == 64 and args.warmup == 8:
             args.steps, args.warmup = 200, 20
         return bench_csr_ablation(args)
-    if args.workload in PROBES:
-        return bench_probe(args)
     if args.workload in DECODE_STEP:
-        if args.steps == 400 and args.warmup == 40:
+        if args.steps == 64 and args.warmup == 8:
             args.steps, args.warmup = 20, 3
         return bench_decode_step(args)
     if args.workload in QUANT_WORKLOADS:
-        if args.steps == 400 and args.warmup == 40:     # the defaults are sized for the microsecond matvecs
+        if args.steps == 64 and args.warmup == 8:     # the defaults are sized for the microsecond matvecs
             args.steps, args.warmup = 20, 3
         return bench_quantize(args)
     shapes, bits, frac, skew, B = WORKLOADS[args.workload]
-    if args.rows_per_wg:
-        sq.sqllm_set_rows_per_workgroup(args.rows_per_wg)
 
     # ---- generate, upload, check parity against the oracle before any timing
     import oracle  # only for the parity gate and the cpu_baseline leg
@@ -436,9 +419,10 @@ def main():
             D.matvec()
 
     G = not args.no_graph
-    sec_cold, wall_cold = time_steps(torch, step_cold, args.steps, args.warmup, G)
-    sec_warm, _ = time_steps(torch, step_warm, args.steps, args.warmup, G)
+    sec_cold, wall_cold = time_steps(torch, step_cold, args.steps, args.warmup, G, args.replays, tag="cold")
+    sec_warm, _ = time_steps(torch, step_warm, args.steps, args.warmup, G, 3)
     launches = args.steps * len(shapes)
+    touched = len({(args.warmup + st) % copies for st in range(args.steps)})
     us_per_matvec = sec_cold / launches * 1e6
     gbs = step_bytes * args.steps / sec_cold / 1e9
 
@@ -492,14 +476,6 @@ def main():
         us_f_own, us_f = None, us_f_torch
     del wring
 
-    if args.copy_calibration:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_()
-        dst = torch.empty_like(src)
-        for _ in range(20):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
     # ---- HBM traffic per launch measured with rocprofv3 counters, if a summary is committed
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic_" + args.workload + ".json")
@@ -532,8 +508,9 @@ def main():
         "ms_per_step": sec_cold / args.steps * 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "layers": [f"{M}x{N}" for M, N in shapes], "bits": bits, "sparse_frac": frac,
-                   "skew": skew, "batch": B, "seed": SEED, "storage": "fp16 tables / CSR values / x / y, fp32 accumulation", "weight_copies_rotated": copies,
-                   "working_set_gb": step_bytes * copies / 1e9, "matvecs_per_step": len(shapes)},
+                   "skew": skew, "batch": B, "seed": SEED, "storage": "fp16 tables / CSR values / x / y, fp32 accumulation", "weight_copies_allocated": copies,
+                   "weight_copies_touched_in_timed_region": touched, "working_set_gb": step_bytes * touched / 1e9, "matvecs_per_step": len(shapes)},
+        "replay_stats_ms_for_K_steps": REPLAY_STATS.get("cold"),
         "effective_gbs": gbs, "pct_of_hbm_roofline": 100.0 * gbs / HBM_PEAK_GBS, "us_per_step": sec_cold / args.steps * 1e6,
         "single_launch_after_idle_us": single_launch_us,
         "warm_us_per_matvec": sec_warm / launches * 1e6, "warm_effective_gbs": step_bytes * args.steps / sec_warm / 1e9,

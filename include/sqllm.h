@@ -7,8 +7,8 @@
  *
  *   D  (M x N)  dense part, stored as b-bit indices (b = 2, 3 or 4) into ONE look-up table of 2^b fp16
  *               values PER OUTPUT ROW:  D[i][j] = lut[i][ idx(i,j) ]
- *               (Sec. 4.3 "the compressed matrices store 3/4-bit indices, which correspond to LUT entries
- *               containing FP16 values"; Sec. 5 "each output channel is assigned a separate lookup table";
+ *               (Sec. 4.3: what is stored are 3- or 4-bit indices, each naming an fp16 entry of a look-up table;
+ *               Sec. 5, quantisation details: every output channel has a table of its own;
  *               App. F quantises to 2 bits with the same format).
  *   S  (M x N)  sparse part in compressed-sparse-row form with fp16 values (Sec. 4.2: outliers and
  *               sensitive values kept in FP16 and stored in CSR).
@@ -38,9 +38,17 @@
  *   term is formed by matrix instructions over groups of 16 rows, and a non-finite x[j][t] then also turns
  *   y[i][t] into NaN for the other rows of the group of a row holding a nonzero in column j (0 x Inf).
  *
- * ERRORS  every function returns an sqllm_status; nothing is enqueued unless SQLLM_OK is returned.  A text
- *   for the last error of the calling thread is available from sqllm_last_error_string().
- *   M == 0 or B*M == 0 -> SQLLM_OK, nothing enqueued.
+ * ERRORS  every function returns an sqllm_status.  Arguments are validated on the host first and nothing is enqueued
+ *   when validation fails.  An entry point that needs several kernel launches (batches of the one-thread-per-row
+ *   kernel beyond 8 columns, more than 65535 rows in the parity exports, the offline pass) can fail in a later
+ *   launch with SQLLM_ERR_HIP after earlier ones were enqueued; its outputs are then undefined.  A text for the last
+ *   error of the calling thread is available from sqllm_last_error_string().
+ *   M == 0 -> SQLLM_OK, nothing enqueued.  N must be positive: N == 0 (an empty sum) is SQLLM_ERR_SHAPE, the caller
+ *   clears y itself.  The library holds gfx950 code only: on any other device the first call that would launch
+ *   returns SQLLM_ERR_DEVICE (the architecture is looked up once per device and remembered).
+ *
+ * THREADS  the library keeps no mutable state other than the per-thread error text and a per-device "architecture
+ *   checked" flag; calls from several threads and on several streams may overlap.
  *
  * ALIGNMENT  qidx and x must be 16-byte aligned; lut 16-byte; y, vals 2-byte; rowptr, cols 4-byte.
  */
@@ -57,7 +65,7 @@ typedef enum {
     SQLLM_OK = 0,
     SQLLM_ERR_NULL = 1,   /* a required pointer is NULL                                   */
     SQLLM_ERR_BITS = 2,   /* bits is not 2, 3 or 4                                        */
-    SQLLM_ERR_SHAPE = 3,  /* M < 0, N <= 0, N % 128 != 0, or N > SQLLM_MAX_N              */
+    SQLLM_ERR_SHAPE = 3,  /* M < 0, N <= 0, N % 128 != 0 (all widths), or N > SQLLM_MAX_N */
     SQLLM_ERR_ALIGN = 4,  /* a pointer violates the alignment rules above                 */
     SQLLM_ERR_NNZ = 5,    /* nnz < 0 or nnz >= 2^31                                       */
     SQLLM_ERR_BATCH = 6,  /* B outside 1..SQLLM_MAX_BATCH                                 */
@@ -141,16 +149,12 @@ int sqllm_quantize_layer(int M, int N, int bits, int max_iter, const void* w, co
 /* Bytes the method moves for one matvec (indices + tables + CSR arrays + x + y); used for GB/s figures.  */
 long long sqllm_algorithmic_bytes(int M, int N, int bits, long long nnz, int B);
 
-/* Machine probe behind the roofline analysis of the matvec kernels: on every compute unit `waves_per_cu` waves (1..16)
- * run `iters` iterations of `lookups` (0 or 16) random look-ups in 64-entry LDS tables -- the access pattern of the
- * 3-bit pair tables -- and `mads` (0, 48, 96 or 128; not both zero) integer multiply-adds.  Timing the call for
- * (16, 0), (0, m) and (16, m) shows how far look-ups and vector-ALU work of different waves overlap.  `out` is a
- * device pointer to at least 4 bytes (practically never written).  No relation to any weight data.               */
-int sqllm_probe_lds_valu(int lookups, int mads, int waves_per_cu, int iters, void* out, void* stream);
-
-/* Tuning knob: rows handled by one workgroup of the matvec kernels (0 = library default; other values are
- * rounded up to 2, 4, 8 or 16).  Affects speed only.  Returns the previous value.  Process-wide, not thread-safe. */
-int sqllm_set_rows_per_workgroup(int rows);
+/* Sec. 4.2 gives the extraction as percentages (outliers by value, plus a share picked by sensitivity); the offline entry
+ * point takes counts.  This host-only helper turns the shares into those counts: half of the outlier share on each tail,
+ * n_lo = n_hi = floor(outlier_frac * M * N / 2), and n_sens = floor(sens_frac * M * N).  Shares must be >= 0 and sum to
+ * less than 1.  The three results are host pointers.                                                                   */
+int sqllm_extraction_counts(int M, int N, double outlier_frac, double sens_frac,
+                            long long* n_lo, long long* n_hi, long long* n_sens);
 
 const char* sqllm_last_error_string(void); /* host pointer, valid until the thread's next failing call */
 const char* sqllm_status_string(int status);

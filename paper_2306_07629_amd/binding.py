@@ -4,7 +4,7 @@ current HIP stream, nothing else.  There is no CPU fallback: a missing library r
 from __future__ import annotations
 
 import ctypes
-import os
+import sys
 
 from . import build as _build
 
@@ -16,8 +16,8 @@ STATUS_NAMES = ["SQLLM_OK", "SQLLM_ERR_NULL", "SQLLM_ERR_BITS", "SQLLM_ERR_SHAPE
 
 EXPORTS = ["sqllm_lut_gemv", "sqllm_csr_spmv", "sqllm_dense_sparse_matvec", "sqllm_csr_spmv_rowwise",
            "sqllm_unpack_indices", "sqllm_dequantize", "sqllm_fp16_gemv", "sqllm_algorithmic_bytes",
-           "sqllm_quantize_workspace_bytes", "sqllm_quantize_layer",
-           "sqllm_probe_lds_valu", "sqllm_set_rows_per_workgroup", "sqllm_last_error_string", "sqllm_status_string", "sqllm_version"]
+           "sqllm_quantize_workspace_bytes", "sqllm_quantize_layer", "sqllm_extraction_counts",
+           "sqllm_last_error_string", "sqllm_status_string", "sqllm_version"]
 
 
 class SqllmError(RuntimeError):
@@ -27,10 +27,11 @@ class SqllmError(RuntimeError):
 
 
 def lib() -> ctypes.CDLL:
-    """Load libsqllm.so (built in-tree by build.py).  Builds it only if no library is there at all."""
+    """Load libsqllm.so (built in-tree by build.py).  A missing library, or one older than its sources, is built first."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_build.LIB):
+        if _build.is_stale():
+            print("paper_2306_07629_amd: libsqllm.so is missing or older than its sources, building it", file=sys.stderr, flush=True)
             _build.build()
         L = ctypes.CDLL(_build.LIB)
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong
@@ -46,14 +47,10 @@ def lib() -> ctypes.CDLL:
         L.sqllm_quantize_workspace_bytes.argtypes = [i32, i32]
         L.sqllm_quantize_workspace_bytes.restype = i64
         L.sqllm_quantize_layer.argtypes = [i32, i32, i32, i32, vp, vp, i64, i64, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp]
-        L.sqllm_probe_lds_valu.argtypes = [i32, i32, i32, i32, vp, vp]
-        L.sqllm_set_rows_per_workgroup.argtypes = [i32]
+        L.sqllm_extraction_counts.argtypes = [i32, i32, ctypes.c_double, ctypes.c_double, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.sqllm_last_error_string.restype = ctypes.c_char_p
         L.sqllm_status_string.argtypes = [i32]
         L.sqllm_status_string.restype = ctypes.c_char_p
-        for name in EXPORTS:
-            if getattr(L, name).restype is ctypes.c_int:
-                pass
         _lib = L
     return _lib
 
@@ -124,12 +121,10 @@ def sqllm_algorithmic_bytes(M, N, bits, nnz, B) -> int:
     return int(lib().sqllm_algorithmic_bytes(M, N, bits, nnz, B))
 
 
-def sqllm_probe_lds_valu(lookups, mads, waves_per_cu, iters, out, stream=None):
-    _check(lib().sqllm_probe_lds_valu(int(lookups), int(mads), int(waves_per_cu), int(iters), _ptr(out), _stream(stream)))
-
-
-def sqllm_set_rows_per_workgroup(rows: int) -> int:
-    return int(lib().sqllm_set_rows_per_workgroup(int(rows)))
+def sqllm_extraction_counts(M, N, outlier_frac, sens_frac):
+    n = [ctypes.c_longlong(0) for _ in range(3)]
+    _check(lib().sqllm_extraction_counts(int(M), int(N), float(outlier_frac), float(sens_frac), *[ctypes.byref(v) for v in n]))
+    return tuple(int(v.value) for v in n)
 
 
 def sqllm_version() -> int:

@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in sqllm.h: argument validation (everything that can be decided without
 // touching the device is decided here, before any HIP call), choice of launch shape, error reporting.
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stdint.h>
 #include <stdarg.h>
 #include <stdio.h>
@@ -12,7 +13,6 @@
 namespace {
 
 thread_local char g_err[256] = "no error";
-int g_rows_per_wg = 0;   // 0 = choose per shape
 
 int fail(int status, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 int fail(int status, const char* fmt, ...) {
@@ -27,6 +27,9 @@ bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t
 
 int check_shape(int M, int N, int B) {
     if (M < 0) return fail(SQLLM_ERR_SHAPE, "M = %d is negative", M);
+    // One rule for every width: a lane of the kernels decodes 32 indices and a wave 2048, and the 16-column kernel walks a row in
+    // windows of 128 columns; 4-bit rows that are whole 16-byte words but not whole 128-column windows (N % 32 == 0 only) are
+    // therefore not accepted.  N == 0 is rejected as well: there is no row to read, the caller can clear y itself.
     if (N <= 0 || N % 128 != 0) return fail(SQLLM_ERR_SHAPE, "N = %d must be a positive multiple of 128", N);
     if (N > SQLLM_MAX_N) return fail(SQLLM_ERR_SHAPE, "N = %d exceeds SQLLM_MAX_N = %d", N, SQLLM_MAX_N);
     if (B < 1 || B > SQLLM_MAX_BATCH) return fail(SQLLM_ERR_BATCH, "B = %d outside 1..%d", B, SQLLM_MAX_BATCH);
@@ -64,29 +67,38 @@ int hip_fail(hipError_t e, const char* what) {
     return fail(SQLLM_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-// Rows handled by one workgroup (the kernels are built for 2, 4, 8 and 16).  Measured on MI355X: when all
-// workgroups of the launch are resident at once (at most 8 waves on each of the 1024 SIMDs) 4 rows is the
-// fastest -- the whole matrix is requested within the first microsecond and the time after the last byte
-// arrives is the decode time of one workgroup, which grows with its row count.  Larger launches run in
-// several generations; there 8 rows keep the dense waves busy for as long as the sparse chain of the block
-// (row pointers -> columns / values -> gathers) takes, so the sparse wave does not hold the block's slot.
-int pick_rows(int M, int waves_per_wg) {
-    if (g_rows_per_wg > 0) return g_rows_per_wg;
-    const long long resident_waves = 256ll * 4 * 8;
-    return ((long long)(M + 3) / 4) * waves_per_wg <= resident_waves ? 4 : 8;
+// The kernels are built for gfx950 only.  The architecture of the current device is looked up once per device (a host-side
+// query, no kernel) and remembered; any other architecture is refused before a launch could fail with a generic HIP error.
+constexpr int kMaxDevices = 64;
+std::atomic<int> g_arch_ok[kMaxDevices];      // 0 unknown, 1 gfx950, -1 something else
+
+int check_device() {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    int state = dev >= 0 && dev < kMaxDevices ? g_arch_ok[dev].load(std::memory_order_relaxed) : 0;
+    if (state == 0) {
+        hipDeviceProp_t prop;
+        e = hipGetDeviceProperties(&prop, dev);
+        if (e != hipSuccess) return hip_fail(e, "hipGetDeviceProperties");
+        state = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : -1;
+        if (dev >= 0 && dev < kMaxDevices) g_arch_ok[dev].store(state, std::memory_order_relaxed);
+        if (state < 0) return fail(SQLLM_ERR_DEVICE, "device %d is %s, this library holds gfx950 code only", dev, prop.gcnArchName);
+    }
+    if (state < 0) return fail(SQLLM_ERR_DEVICE, "device %d is not a gfx950 GPU", dev);
+    return SQLLM_OK;
 }
 
 int run_matvec(int M, int N, int bits, long long nnz, int B, const void* qidx, const void* lut, const int* rowptr,
                const int* cols, const void* vals, const void* x, void* y, int accumulate, void* stream) {
     if (M == 0) return SQLLM_OK;
+    int st;
+    if ((st = check_device())) return st;
     sqllm::MatvecArgs g;
     memset(&g, 0, sizeof g);
     g.M = M; g.N = N; g.bits = bits; g.B = B; g.bt0 = 0; g.bn = B;
     g.accumulate = accumulate; g.nnz = nnz;
     g.qidx = qidx; g.lut = lut; g.rowptr = rowptr; g.cols = cols; g.vals = vals; g.x = x; g.y = y;
-    const int waves = qidx ? (N + 2047) / 2048 + (nnz > 0 ? 1 : 0) : 4;
-    g.rows_per_wg = pick_rows(M, waves);
-    g.mfma_batch = g_rows_per_wg == 0;       // an explicit rows-per-workgroup request selects the vector-ALU kernels
     const hipError_t e = sqllm::launch_matvec(g, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "matvec launch");
     return SQLLM_OK;
@@ -123,6 +135,7 @@ int sqllm_csr_spmv_rowwise(int M, int N, long long nnz, int B, const int* rowptr
     int st;
     if ((st = check_shape(M, N, B)) || (st = check_sparse(nnz, rowptr, cols, vals)) || (st = check_xy(x, y))) return st;
     if (M == 0) return SQLLM_OK;
+    if ((st = check_device())) return st;
     sqllm::MatvecArgs g;
     memset(&g, 0, sizeof g);
     g.M = M; g.N = N; g.bits = 3; g.B = B; g.bn = B; g.accumulate = accumulate; g.nnz = nnz;
@@ -138,6 +151,7 @@ int sqllm_unpack_indices(int M, int N, int bits, const void* qidx, void* idx_out
     if (!qidx || !idx_out) return fail(SQLLM_ERR_NULL, "qidx / idx_out must not be NULL");
     if (misaligned(qidx, 16)) return fail(SQLLM_ERR_ALIGN, "qidx must be 16-byte aligned");
     if (M == 0) return SQLLM_OK;
+    if ((st = check_device())) return st;
     const hipError_t e = sqllm::launch_decode(M, N, bits, qidx, nullptr, idx_out, nullptr, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "unpack launch");
     return SQLLM_OK;
@@ -149,6 +163,7 @@ int sqllm_dequantize(int M, int N, int bits, const void* qidx, const void* lut, 
     if (!w_out) return fail(SQLLM_ERR_NULL, "w_out must not be NULL");
     if (misaligned(w_out, 2)) return fail(SQLLM_ERR_ALIGN, "w_out must be 2-byte aligned");
     if (M == 0) return SQLLM_OK;
+    if ((st = check_device())) return st;
     const hipError_t e = sqllm::launch_decode(M, N, bits, qidx, lut, nullptr, w_out, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "dequantize launch");
     return SQLLM_OK;
@@ -163,6 +178,7 @@ int sqllm_fp16_gemv(int M, int N, int B, const void* w, const void* x, void* y, 
     int st;
     if ((st = check_xy(x, y))) return st;
     if (M == 0) return SQLLM_OK;
+    if ((st = check_device())) return st;
     const hipError_t e = sqllm::launch_fp16_gemv(M, N, B, w, x, y, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "fp16_gemv launch");
     return SQLLM_OK;
@@ -179,9 +195,9 @@ long long sqllm_quantize_workspace_bytes(int M, int N) {
     return (long long)sqllm::quantize_workspace_bytes();
 }
 
-int sqllm_quantize_layer(int M, int N, int bits, int max_iter, const void* w, const void* sens,
-                         long long n_lo, long long n_hi, long long n_sens, void* workspace, long long workspace_bytes,
-                         void* qidx, void* lut, int* rowptr, int* cols, void* vals, int* iters, void* stream) {
+namespace {
+int run_quantize(int M, int N, int bits, int max_iter, const void* w, const void* sens, long long n_lo, long long n_hi, long long n_sens,
+                 void* workspace, void* qidx, void* lut, int* rowptr, int* cols, void* vals, int* iters, void* stream) {
     int st;
     if ((st = check_bits(bits)) || (st = check_shape(M, N, 1))) return st;
     if (M == 0) return SQLLM_OK;
@@ -192,11 +208,10 @@ int sqllm_quantize_layer(int M, int N, int bits, int max_iter, const void* w, co
         return fail(SQLLM_ERR_NNZ, "extraction counts (%lld, %lld, %lld) out of range for %lld weights", n_lo, n_hi, n_sens, total);
     if (!w || !sens || !workspace || !qidx || !lut || !rowptr) return fail(SQLLM_ERR_NULL, "a required pointer is NULL");
     if (n_lo + n_hi + n_sens > 0 && (!cols || !vals)) return fail(SQLLM_ERR_NULL, "cols / vals are NULL although entries may be extracted");
-    if (workspace_bytes < (long long)sqllm::quantize_workspace_bytes())
-        return fail(SQLLM_ERR_SHAPE, "workspace of %lld bytes, %lld needed", workspace_bytes, (long long)sqllm::quantize_workspace_bytes());
     if (((uintptr_t)w | (uintptr_t)sens | (uintptr_t)qidx | (uintptr_t)lut) & 15) return fail(SQLLM_ERR_ALIGN, "w, sens, qidx and lut must be 16-byte aligned");
     if (((uintptr_t)workspace | (uintptr_t)rowptr | (uintptr_t)cols | (uintptr_t)iters) & 3) return fail(SQLLM_ERR_ALIGN, "workspace, rowptr, cols and iters must be 4-byte aligned");
     if ((uintptr_t)vals & 1) return fail(SQLLM_ERR_ALIGN, "vals must be 2-byte aligned");
+    if ((st = check_device())) return st;
     sqllm::QuantArgs a;
     memset(&a, 0, sizeof a);
     a.M = M; a.N = N; a.bits = bits; a.max_iter = max_iter; a.n_lo = n_lo; a.n_hi = n_hi; a.n_sens = n_sens;
@@ -205,23 +220,25 @@ int sqllm_quantize_layer(int M, int N, int bits, int max_iter, const void* w, co
     if (e != hipSuccess) return hip_fail(e, "quantize launch");
     return SQLLM_OK;
 }
+}  // namespace
 
-int sqllm_probe_lds_valu(int lookups, int mads, int waves_per_cu, int iters, void* out, void* stream) {
-    if (!((lookups == 16 && (mads == 0 || mads == 48 || mads == 96 || mads == 128)) || (lookups == 0 && (mads == 48 || mads == 96 || mads == 128))))
-        return fail(SQLLM_ERR_SHAPE, "probe: (lookups, mads) = (%d, %d) is not one of the built combinations", lookups, mads);
-    if (waves_per_cu < 1 || waves_per_cu > 16) return fail(SQLLM_ERR_SHAPE, "probe: waves_per_cu = %d outside 1..16", waves_per_cu);
-    if (iters < 1 || iters > 1000000) return fail(SQLLM_ERR_SHAPE, "probe: iters = %d outside 1..1000000", iters);
-    if (!out) return fail(SQLLM_ERR_NULL, "probe: out must not be NULL");
-    if (misaligned(out, 4)) return fail(SQLLM_ERR_ALIGN, "probe: out must be 4-byte aligned");
-    const hipError_t e = sqllm::launch_probe_lds_valu(lookups, mads, waves_per_cu, iters, out, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) return hip_fail(e, "probe launch");
-    return SQLLM_OK;
+int sqllm_quantize_layer(int M, int N, int bits, int max_iter, const void* w, const void* sens,
+                         long long n_lo, long long n_hi, long long n_sens, void* workspace, long long workspace_bytes,
+                         void* qidx, void* lut, int* rowptr, int* cols, void* vals, int* iters, void* stream) {
+    if (M != 0 && workspace && workspace_bytes < (long long)sqllm::quantize_workspace_bytes())
+        return fail(SQLLM_ERR_SHAPE, "workspace of %lld bytes, %lld needed", workspace_bytes, (long long)sqllm::quantize_workspace_bytes());
+    return run_quantize(M, N, bits, max_iter, w, sens, n_lo, n_hi, n_sens, workspace, qidx, lut, rowptr, cols, vals, iters, stream);
 }
 
-int sqllm_set_rows_per_workgroup(int rows) {
-    const int old = g_rows_per_wg;
-    g_rows_per_wg = rows < 0 ? 0 : (rows > 64 ? 64 : rows);
-    return old;
+int sqllm_extraction_counts(int M, int N, double outlier_frac, double sens_frac, long long* n_lo, long long* n_hi, long long* n_sens) {
+    if (!n_lo || !n_hi || !n_sens) return fail(SQLLM_ERR_NULL, "n_lo / n_hi / n_sens must not be NULL");
+    if (M < 0 || N < 0) return fail(SQLLM_ERR_SHAPE, "M = %d, N = %d: negative", M, N);
+    if (!(outlier_frac >= 0.0 && sens_frac >= 0.0 && outlier_frac + sens_frac < 1.0))
+        return fail(SQLLM_ERR_NNZ, "shares %g + %g outside [0, 1)", outlier_frac, sens_frac);
+    const double total = (double)M * (double)N;
+    *n_lo = *n_hi = (long long)(outlier_frac * total / 2.0);      // half of the outlier share on each tail
+    *n_sens = (long long)(sens_frac * total);
+    return SQLLM_OK;
 }
 
 const char* sqllm_last_error_string(void) { return g_err; }

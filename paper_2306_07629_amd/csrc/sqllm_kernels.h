@@ -6,10 +6,8 @@ namespace sqllm {
 
 struct MatvecArgs {
     int M, N, bits, B;
-    int bt0, bn;            // batch columns [bt0, bt0 + bn) are computed by this launch (bn <= 4)
-    int rows_per_wg;        // requested rows per workgroup; the launcher rounds it to 2, 4, 8 or 16
+    int bt0, bn;            // one-thread-per-row CSR kernel only: batch columns [bt0, bt0 + bn) are computed by this launch (bn <= 8)
     int accumulate;
-    int mfma_batch;         // nonzero: windows of four activation columns go to the matrix-core kernel
     long long nnz;
     const void* qidx;       // nullptr -> no dense term
     const void* lut;
@@ -41,6 +39,5 @@ hipError_t launch_matvec(const MatvecArgs& g, hipStream_t s);
 hipError_t launch_csr_rowwise(const MatvecArgs& g, hipStream_t s);
 hipError_t launch_decode(int M, int N, int bits, const void* qidx, const void* lut, void* idx_out, void* w_out, hipStream_t s);
 hipError_t launch_fp16_gemv(int M, int N, int B, const void* w, const void* x, void* y, hipStream_t s);
-hipError_t launch_probe_lds_valu(int lookups, int mads, int waves_per_cu, int iters, void* out, hipStream_t s);
 
 }  // namespace sqllm

@@ -4,7 +4,7 @@
 // one fp16 table per output row, S in CSR with fp16 values.  The storage format is described in sqllm.h.
 //
 // Work decomposition of the matvec kernel
-//   * A workgroup owns R consecutive rows (R = 2, 4, 8 or 16, compile time) and all N columns.
+//   * A workgroup owns R consecutive rows (R = 4 or 8, compile time) and all N columns.
 //   * Dense waves: wave w owns the 2048-column slice [2048 w, 2048 w + 2048): lane l keeps the 32 activations
 //     x[2048 w + 32 l .. +32) in registers for the whole kernel (x is read once per workgroup) and, per row,
 //     loads its 32 indices (12 bytes for b = 3, 16 bytes for b = 4; the wave reads 768 / 1024 contiguous
@@ -149,86 +149,13 @@ __device__ __forceinline__ void build_tables(u32* __restrict__ tables, const uin
 }
 
 // ---------------------------------------------------------------------------------------------- x in registers
-// xr[t][p] = (x[j0 + 2p][t], x[j0 + 2p + 1][t]) for the lane's 32 columns j0 .. j0 + 31 (j0 is in range).
-// x points at the first live batch column; B is the row stride of x, bn the number of live columns.
-template <int NB>
-__device__ __forceinline__ void load_x(const uint16_t* __restrict__ x, int B, int bn, int j0, u32 (&xr)[NB][16]) {
-    if (NB == 1 && B == 1) {
-        const u32x4* src = reinterpret_cast<const u32x4*>(x + j0);
+// xr[p] = (x[j0 + 2p], x[j0 + 2p + 1]) for the lane's 32 columns j0 .. j0 + 31 (j0 is in range, x is one column).
+__device__ __forceinline__ void load_x(const uint16_t* __restrict__ x, int j0, u32 (&xr)[16]) {
+    const u32x4* src = reinterpret_cast<const u32x4*>(x + j0);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const u32x4 v = src[k];
-            xr[0][4 * k + 0] = v.x; xr[0][4 * k + 1] = v.y; xr[0][4 * k + 2] = v.z; xr[0][4 * k + 3] = v.w;
-        }
-    } else if (NB >= 2) {
-        // handled by load_x_staged (coalesced loads transposed through LDS)
-    } else {
-        // one column of a wider batch: one 16-bit load per value
-#pragma unroll
-        for (int p = 0; p < 16; ++p) {
-            const u32 lo = x[(size_t)(j0 + 2 * p) * B], hi = x[(size_t)(j0 + 2 * p + 1) * B];
-            xr[0][p] = lo | (hi << 16);
-        }
-    }
-    (void)bn;
-}
-
-// Batched activations (NB = 2 or 4 live columns, even row stride B): consecutive lanes load consecutive rows of
-// x (coalesced), the rows are transposed through a wave-private LDS buffer, and every lane ends up with
-// xr[t][p] = (x[j][t], x[j + 1][t]) for its own 32 rows j = slice_base + 32 lane + 2p.  The slice is staged in
-// one round (whole slice, 64 lane groups) when LDS allows, else four rounds of 512 rows (16 lane groups); the
-// 16-byte pad per lane group keeps the 128-bit reads free of bank conflicts.  Rows past N load row N - 1 (their lanes' activations
-// are zeroed by the caller).
-template <int NB, int XG>
-struct XStage {
-    static constexpr int kGroupBytes = 64 * NB + 16;       // 32 rows * NB halves + pad
-    static constexpr int kBytes = XG * kGroupBytes;        // per wave; XG = lane groups staged per round (16 or 64)
-};
-
-template <int NB, int XG>
-__device__ __forceinline__ void load_x_staged(const uint16_t* __restrict__ x, int B, int N, int slice_base, int lane, char* __restrict__ buf, u32 (&xr)[NB][16]) {
-    constexpr int RW = NB / 2;                              // dwords per row window
-    constexpr int GB = XStage<NB, XG>::kGroupBytes;
-    constexpr int ROUNDS = 64 / XG, LOADS = XG / 2;         // a round stages XG * 32 rows with XG / 2 loads per lane
-#pragma unroll
-    for (int t = 0; t < NB; ++t)
-#pragma unroll
-        for (int p = 0; p < 16; ++p) xr[t][p] = 0;
-#pragma unroll 1
-    for (int r = 0; r < ROUNDS; ++r) {
-        u32 v[LOADS][RW];
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int row = min(slice_base + XG * 32 * r + 64 * i + lane, N - 1);
-            const u32* src = reinterpret_cast<const u32*>(x + (size_t)row * B);
-#pragma unroll
-            for (int h = 0; h < RW; ++h) v[i][h] = src[h];
-        }
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int lr = 64 * i + lane;                    // local row: group lr / 32, row lr % 32
-            u32* dst = reinterpret_cast<u32*>(buf + (lr >> 5) * GB + (lr & 31) * (NB * 2));
-#pragma unroll
-            for (int h = 0; h < RW; ++h) dst[h] = v[i][h];
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        if (lane / XG == r) {
-            const u32* src = reinterpret_cast<const u32*>(buf + (lane % XG) * GB);
-#pragma unroll
-            for (int p = 0; p < 16; ++p) {
-#pragma unroll
-                for (int h = 0; h < RW; ++h) {
-                    const u32 a = src[(2 * p) * RW + h], b = src[(2 * p + 1) * RW + h];   // rows 2p and 2p + 1
-                    xr[2 * h][p] = __builtin_amdgcn_perm(b, a, 0x05040100u);             // (a.lo, b.lo)
-                    xr[2 * h + 1][p] = __builtin_amdgcn_perm(b, a, 0x07060302u);         // (a.hi, b.hi)
-                }
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int k = 0; k < 4; ++k) {
+        const u32x4 v = src[k];
+        xr[4 * k + 0] = v.x; xr[4 * k + 1] = v.y; xr[4 * k + 2] = v.z; xr[4 * k + 3] = v.w;
     }
 }
 
@@ -242,29 +169,27 @@ __device__ __forceinline__ void lookup_chunk(const LaneChunk<BITS>& c, const u32
     for (int p = 0; p < 16; ++p) w[p] = *reinterpret_cast<const u32*>(tb + a[p]);
 }
 
-// 16 * NB packed dot products (two fp16 products each, fp32 accumulate); two accumulator chains per column
-template <int NB>
-__device__ __forceinline__ void dot_chunk(const u32 (&w)[16], const u32 (&xr)[NB][16], float (&acc)[NB]) {
+// 16 packed dot products (two fp16 products each, fp32 accumulate) in two accumulator chains
+__device__ __forceinline__ float dot_chunk(const u32 (&w)[16], const u32 (&xr)[16]) {
+    float a0 = 0.f, a1 = 0.f;
 #pragma unroll
-    for (int t = 0; t < NB; ++t) {
-        float a0 = 0.f, a1 = 0.f;
-#pragma unroll
-        for (int p = 0; p < 16; p += 2) {
-            a0 = __builtin_amdgcn_fdot2(as_half2(w[p]), as_half2(xr[t][p]), a0, false);
-            a1 = __builtin_amdgcn_fdot2(as_half2(w[p + 1]), as_half2(xr[t][p + 1]), a1, false);
-        }
-        acc[t] = a0 + a1;
+    for (int p = 0; p < 16; p += 2) {
+        a0 = __builtin_amdgcn_fdot2(as_half2(w[p]), as_half2(xr[p]), a0, false);
+        a1 = __builtin_amdgcn_fdot2(as_half2(w[p + 1]), as_half2(xr[p + 1]), a1, false);
     }
+    return a0 + a1;
 }
 
-// Joint reduction of C per-lane values over the lanes of each 16-lane row (C = 4, 8 or 16).  On return v[0]
-// of lane l holds, for class (l mod C), the sum of the input v[l mod C] over the 16 lanes of l's row.
-// log2(C) butterfly steps halve the number of live values; 3 VALU per produced value instead of a full
-// 6-step reduction per input.
+// Joint reduction of C per-lane values over the lanes of each 16-lane row (C = 4 or 8).  On return v[0] holds, in the lanes
+// named by row_block_slot(), the sum of one input v[c] over the 16 lanes of the lane's row.  Butterfly steps halve the number of
+// live values (3 VALU per produced value instead of a full 4-step reduction per input).  The association of the additions is
+// the same for every c and both C -- quads first (lane ^ 1, lane ^ 2), then quad k with quad k ^ 2, then the two pair sums:
+// ((q0 + q2) + (q1 + q3)) up to commutativity -- so a row's sum does not depend on how many rows its workgroup owns, and
+// projections stacked into one call give bit for bit the dense term of separate calls.
 template <int C>
 __device__ __forceinline__ void row_block_reduce(float (&v)[C], int lane) {
-    static_assert(C == 2 || C == 4 || C == 8 || C == 16, "block size");
-    {   // lane bit 0, partner lane ^ 1
+    static_assert(C == 4 || C == 8, "block size");
+    {   // lane bit 0, partner lane ^ 1: v[k] <- class 2 k + (lane & 1)
         const bool hi = lane & 1;
 #pragma unroll
         for (int k = 0; k < C / 2; ++k) {
@@ -272,34 +197,29 @@ __device__ __forceinline__ void row_block_reduce(float (&v)[C], int lane) {
             v[k] = keep + dpp_f<kQuadXor1>(0.f, send);
         }
     }
-    if constexpr (C >= 4) {   // lane bit 1, partner lane ^ 2
+    {   // lane bit 1, partner lane ^ 2: v[k] <- class 4 k + (lane & 3)
         const bool hi = lane & 2;
 #pragma unroll
         for (int k = 0; k < C / 4; ++k) {
             const float keep = hi ? v[2 * k + 1] : v[2 * k], send = hi ? v[2 * k] : v[2 * k + 1];
             v[k] = keep + dpp_f<kQuadXor2>(0.f, send);
         }
-    } else {
-        v[0] += dpp_f<kQuadXor2>(0.f, v[0]);
     }
-    if constexpr (C >= 8) {   // lane bit 2: values travel by a rotation of 4 lanes within the row
-        const bool hi = lane & 4;
-#pragma unroll
-        for (int k = 0; k < C / 8; ++k) {
-            const float keep = hi ? v[2 * k + 1] : v[2 * k], send = hi ? v[2 * k] : v[2 * k + 1];
-            v[k] = keep + dpp_f<kRowRor4>(0.f, send);
-        }
-    } else {
-        v[0] += dpp_f<kRowRor4>(0.f, v[0]);
-    }
-    if constexpr (C == 16) {  // lane bit 3: rotation of 8 lanes
+    // lane bit 3 (a rotation by 8 lanes pairs lane l with lane l ^ 8): quads k and k ^ 2
+    if constexpr (C == 8) {
         const bool hi = lane & 8;
         const float keep = hi ? v[1] : v[0], send = hi ? v[0] : v[1];
-        v[0] = keep + dpp_f<kRowRor8>(0.f, send);
+        v[0] = keep + dpp_f<kRowRor8>(0.f, send);            // lanes 0..7: class lane & 3; lanes 8..15: class 4 + (lane & 3)
     } else {
         v[0] += dpp_f<kRowRor8>(0.f, v[0]);
     }
+    // lane bit 2: a rotation by 4 lanes hands quad k the pair sum of quad k - 1, which holds the same class for odd k
+    v[0] += dpp_f<kRowRor4>(0.f, v[0]);
 }
+// lane of a 16-lane row that holds class c after row_block_reduce<C>: a lane of quad 1 (c < 4) or quad 3 (c >= 4)
+__device__ __forceinline__ bool row_block_valid(int lane) { return (lane & 4) != 0; }
+template <int C>
+__device__ __forceinline__ int row_block_class(int lane) { return (C == 8 && (lane & 8)) ? 4 + (lane & 3) : (lane & 3); }
 
 // ---------------------------------------------------------------------------------------------- sparse term
 // Balanced CSR (cf. Sec. 4.3).  The nonzeros of the block's R rows are ONE contiguous range [P0, P1) of the
@@ -310,12 +230,11 @@ __device__ __forceinline__ void row_block_reduce(float (&v)[C], int lane) {
 // (which the dense decode of the same wave overlaps).  Products are combined per row inside the wave (plain
 // DPP reduction when a batch lies in one row, segmented DPP scan otherwise) and only the last lane of a row
 // segment adds to the wave's private LDS slot of that row: no floating-point atomics, fixed summation order.
-template <int NB, int UB>
+template <int UB>
 struct SparseRegs {
-    static constexpr int XW = (NB + 1) / 2;   // dwords holding the NB gathered activations of one nonzero
     int c[UB];
     uint16_t vb[UB];
-    u32 xw[UB][XW];
+    uint16_t xv[UB];
 };
 
 struct SparseRange {
@@ -324,8 +243,8 @@ struct SparseRange {
 
 // Loads of one round are unconditional (indices clamped into [P0, P1), surplus lanes and batches are masked
 // in the reduction), so that all of them are in flight at once.
-template <int NB, int UB>
-__device__ __forceinline__ void sparse_issue_cols_vals(const MatvecArgs& g, const SparseRange& sr, int b0, int NW, int lane, SparseRegs<NB, UB>& q) {
+template <int UB>
+__device__ __forceinline__ void sparse_issue_cols_vals(const MatvecArgs& g, const SparseRange& sr, int b0, int NW, int lane, SparseRegs<UB>& q) {
     const int* __restrict__ cols = g.cols;
     const uint16_t* __restrict__ vals = static_cast<const uint16_t*>(g.vals);
 #pragma unroll
@@ -336,32 +255,20 @@ __device__ __forceinline__ void sparse_issue_cols_vals(const MatvecArgs& g, cons
     }
 }
 
-// x points at the first live batch column; with NB >= 2 the row stride is even and the window starts at a
-// multiple of 4 columns, so the NB activations of a nonzero are whole dwords
-template <int NB, int UB>
-__device__ __forceinline__ void sparse_issue_gathers(const MatvecArgs& g, const uint16_t* __restrict__ x, SparseRegs<NB, UB>& q) {
+template <int UB>
+__device__ __forceinline__ void sparse_issue_gathers(const uint16_t* __restrict__ x, SparseRegs<UB>& q) {
 #pragma unroll
-    for (int k = 0; k < UB; ++k) {
-        if constexpr (NB == 1) {
-            q.xw[k][0] = x[(size_t)q.c[k] * g.B];
-        } else {
-            const u32* src = reinterpret_cast<const u32*>(x + (size_t)q.c[k] * g.B);
-#pragma unroll
-            for (int h = 0; h < NB / 2; ++h) q.xw[k][h] = src[2 * h < g.bn ? h : 0];   // a narrower window re-reads its first dword (never past the row)
-        }
-    }
+    for (int k = 0; k < UB; ++k) q.xv[k] = x[q.c[k]];
 }
 
 // LDS float add without a returned value: queued in order behind the wave's earlier LDS operations.  Only one
 // wave ever touches a given slot and its lanes address distinct slots, so the summation order is fixed.
 __device__ __forceinline__ void lds_add(float* slot, float v) { (void)__hip_atomic_fetch_add(slot, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
 
-template <int NB, int R, int UB>
-__device__ __forceinline__ void sparse_reduce(const SparseRange& sr, const int (&rp)[R + 1], int b0, int NW, int lane, const SparseRegs<NB, UB>& q, float* __restrict__ slots) {
+template <int R, int UB>
+__device__ __forceinline__ void sparse_reduce(const SparseRange& sr, const int (&rp)[R + 1], int b0, int NW, int lane, const SparseRegs<UB>& q, float* __restrict__ slots) {
     int carry_row = -1;                                              // uniform: row whose sum is still in registers
-    float carry[NB];
-#pragma unroll
-    for (int t = 0; t < NB; ++t) carry[t] = 0.f;
+    float carry = 0.f;
 #pragma unroll
     for (int k = 0; k < UB; ++k) {
         const int b = b0 + k * NW;
@@ -369,26 +276,18 @@ __device__ __forceinline__ void sparse_reduce(const SparseRange& sr, const int (
             const int p_first = sr.P0 + b * kWave, p_last = min(p_first + kWave, sr.P1) - 1;
             const int p = p_first + lane;
             const bool ok = p <= p_last;
-            float v[NB];
-#pragma unroll
-            for (int t = 0; t < NB; ++t)
-                v[t] = ok ? half_bits_to_float(q.vb[k]) * half_bits_to_float((uint16_t)(q.xw[k][t >> 1] >> (16 * (t & 1)))) : 0.f;
+            float v = ok ? half_bits_to_float(q.vb[k]) * half_bits_to_float(q.xv[k]) : 0.f;
             int row_first = 0, row_last = 0;                         // rows of the batch's first / last nonzero
 #pragma unroll
             for (int i = 1; i < R; ++i) { row_first += (p_first >= rp[i]) ? 1 : 0; row_last += (p_last >= rp[i]) ? 1 : 0; }
             if (row_first == row_last) {
                 // the whole batch lies in one row: plain wave reduction, summed in registers across batches
                 if (carry_row != row_first) {
-                    if (carry_row >= 0 && lane == kWave - 1) {
-#pragma unroll
-                        for (int t = 0; t < NB; ++t) lds_add(slots + carry_row * NB + t, carry[t]);
-                    }
+                    if (carry_row >= 0 && lane == kWave - 1) lds_add(slots + carry_row, carry);
                     carry_row = row_first;
-#pragma unroll
-                    for (int t = 0; t < NB; ++t) carry[t] = 0.f;
+                    carry = 0.f;
                 }
-#pragma unroll
-                for (int t = 0; t < NB; ++t) carry[t] += wave_sum_to_lane63(v[t]);
+                carry += wave_sum_to_lane63(v);
             } else {
                 int row = 0;                                         // number of i in 1..R-1 with rp[i] <= p
 #pragma unroll
@@ -398,10 +297,8 @@ __device__ __forceinline__ void sparse_reduce(const SparseRange& sr, const int (
 #define SQ_SEG_STEP(CTRL, MASK)                                                        \
                 {                                                                      \
                     const int r_up = dpp_i<CTRL, MASK>(-1, row);                       \
-                    _Pragma("unroll") for (int t = 0; t < NB; ++t) {                   \
-                        const float v_up = dpp_f<CTRL, MASK>(0.f, v[t]);               \
-                        v[t] += (r_up == row) ? v_up : 0.f;                            \
-                    }                                                                  \
+                    const float v_up = dpp_f<CTRL, MASK>(0.f, v);                      \
+                    v += (r_up == row) ? v_up : 0.f;                                   \
                 }
                 SQ_SEG_STEP(kRowShr1, 0xF)
                 SQ_SEG_STEP(kRowShr2, 0xF)
@@ -411,29 +308,23 @@ __device__ __forceinline__ void sparse_reduce(const SparseRange& sr, const int (
                 SQ_SEG_STEP(kRowBcast31, 0xC)
 #undef SQ_SEG_STEP
                 const int row_next = dpp_i<kWaveShl1>(-2, row);
-                if (ok && row_next != row) {                          // last lane of its row segment
-#pragma unroll
-                    for (int t = 0; t < NB; ++t) lds_add(slots + row * NB + t, v[t]);
-                }
+                if (ok && row_next != row) lds_add(slots + row, v);  // last lane of its row segment
             }
         }
     }
-    if (carry_row >= 0 && lane == kWave - 1) {
-#pragma unroll
-        for (int t = 0; t < NB; ++t) lds_add(slots + carry_row * NB + t, carry[t]);
-    }
+    if (carry_row >= 0 && lane == kWave - 1) lds_add(slots + carry_row, carry);
 }
 
-template <int NB, int R, int U>
+template <int R, int U>
 __device__ __forceinline__ void sparse_round(const MatvecArgs& g, const uint16_t* __restrict__ x, const SparseRange& sr, const int (&rp)[R + 1],
                                              int b0, int NW, int lane, float* __restrict__ slots) {
-    SparseRegs<NB, U> q;
-    sparse_issue_cols_vals<NB, U>(g, sr, b0, NW, lane, q);
-    sparse_issue_gathers<NB, U>(g, x, q);
-    sparse_reduce<NB, R, U>(sr, rp, b0, NW, lane, q, slots);
+    SparseRegs<U> q;
+    sparse_issue_cols_vals<U>(g, sr, b0, NW, lane, q);
+    sparse_issue_gathers<U>(x, q);
+    sparse_reduce<R, U>(sr, rp, b0, NW, lane, q, slots);
 }
 
-// ---------------------------------------------------------------------------------------------- the matvec kernel
+// ---------------------------------------------------------------------------------------------- the matvec kernel (one activation column)
 // grid.x = ceil(M / R); block = (W + S) waves.  W = ceil(N / 2048) dense waves (0 without a dense term), wave w
 // owning column slice w; S sparse waves (1 next to a dense term, kSparseOnlyWaves alone, 0 when nnz == 0).
 // The sparse wave works through the first UB batches of the block's nonzeros while the dense waves stream
@@ -443,25 +334,24 @@ __device__ __forceinline__ void sparse_round(const MatvecArgs& g, const uint16_t
 // neutralised by zero activations / by not being stored.
 constexpr int kSparseOnlyWaves = 4;
 
-template <int NB, int R>
+template <int R>
 __device__ __forceinline__ void load_row_pointers(const MatvecArgs& g, int r0, int nrows, bool sparse, int (&rp)[R + 1], SparseRange& sr) {
 #pragma unroll
     for (int k = 0; k <= R; ++k) rp[k] = sparse ? g.rowptr[r0 + min(k, nrows)] : 0;   // uniform -> scalar loads
     sr.P0 = rp[0]; sr.P1 = rp[R]; sr.nbatch = (sr.P1 - sr.P0 + kWave - 1) / kWave;
 }
 
-template <int BITS, int NB, int R, int D, int MAXT, int XG>
-__global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
-    static_assert(D >= 2 && D <= R, "prefetch depth");
+template <int BITS, int R, int D>
+__global__ void __launch_bounds__(1024) matvec_kernel(MatvecArgs g) {
+    static_assert(D >= 2 && D <= R && (R == 4 || R == 8), "prefetch depth, rows per workgroup");
     constexpr int E = TableShape<BITS>::kEntries, K = 1 << BITS;
     constexpr int kRawUnit = TableShape<BITS>::kRawUnit;             // bytes of fp16 tables one lane fetches (16, or 8 for b = 2)
     constexpr int UB = 8;                                            // sparse batches per wave and round
     constexpr int TD = TableShape<BITS>::kTableDwords;
     __shared__ __align__(8) u32 tables[R * TD];
     __shared__ __align__(16) uint16_t raw[R * K];
-    __shared__ float part[kMaxDenseWaves * 4 * R * NB];              // dense:  [wave][16-lane row][r][t]
-    __shared__ float spart[(kMaxDenseWaves + 1) * R * NB];           // sparse: [wave][r][t]
-    extern __shared__ __align__(16) char xstage[];                   // batched launches: W * XStage<NB, XG>::kBytes
+    __shared__ float part[kMaxDenseWaves * 4 * R];                   // dense:  [wave][16-lane row][r]
+    __shared__ float spart[(kMaxDenseWaves + 1) * R];                // sparse: [wave][r]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
     const int NW = blockDim.x >> 6;
@@ -469,14 +359,13 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
     const int W = dense ? (g.N + kSliceCols - 1) / kSliceCols : 0;
     const int r0 = blockIdx.x * R;
     const int nrows = min(R, g.M - r0);
-    const int B = g.B, bn = g.bn;
-    const uint16_t* __restrict__ x = static_cast<const uint16_t*>(g.x) + g.bt0;
+    const uint16_t* __restrict__ x = static_cast<const uint16_t*>(g.x);
 
     int rp[R + 1];
     SparseRange sr;
-    load_row_pointers<NB, R>(g, r0, nrows, sparse, rp, sr);          // consumed late by the dense waves
-    float* myslots = spart + wave * R * NB;
-    if (lane < R * NB) myslots[lane] = 0.f;
+    load_row_pointers<R>(g, r0, nrows, sparse, rp, sr);              // consumed late by the dense waves
+    float* myslots = spart + wave * R;
+    if (lane < R) myslots[lane] = 0.f;
     int next_batch = 0;                                              // first batch not yet handled (uniform)
 
     if (wave < W) {
@@ -499,9 +388,8 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
         const int j0 = wave * kSliceCols + lane * kLaneElems;
         const bool live = j0 < g.N;
         const int j0c = live ? j0 : g.N - kLaneElems;
-        u32 xr[NB][16];
-        if constexpr (NB == 1) load_x<NB>(x, B, bn, j0c, xr);
-        else load_x_staged<NB, XG>(x, B, g.N, wave * kSliceCols, lane, xstage + wave * XStage<NB, XG>::kBytes, xr);
+        u32 xr[16];
+        load_x(x, j0c, xr);
         const size_t row_dwords = (size_t)g.N * BITS / 32;
         const u32* __restrict__ qlane = static_cast<const u32*>(g.qidx) + (size_t)(j0c / 32) * BITS;
         LaneChunk<BITS> c[R];
@@ -509,9 +397,7 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
         for (int u = 0; u < D; ++u) c[u] = load_chunk<BITS>(qlane + (size_t)min(r0 + u, g.M - 1) * row_dwords);
         if (!live) {
 #pragma unroll
-            for (int t = 0; t < NB; ++t)
-#pragma unroll
-                for (int p = 0; p < 16; ++p) xr[t][p] = 0;
+            for (int p = 0; p < 16; ++p) xr[p] = 0;
         }
         if (my_rows > 0) {                                            // uniform
             if (lane < my_rows * LPR) {
@@ -526,7 +412,7 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
         __syncthreads();
         // software pipeline: the look-ups of row u + 1 are in flight while the products of row u are formed;
         // row u + D of the index stream is requested when row u has been handed to the look-ups
-        float acc[NB][R];
+        float acc[R];
         u32 w[2][16];
         lookup_chunk<BITS>(c[0], tables, w[0]);
         if constexpr (D < R) c[D] = load_chunk<BITS>(qlane + (size_t)min(r0 + D, g.M - 1) * row_dwords);
@@ -536,62 +422,48 @@ __global__ void __launch_bounds__(MAXT) matvec_kernel(MatvecArgs g) {
                 lookup_chunk<BITS>(c[u + 1], tables + (u + 1) * TD, w[(u + 1) & 1]);
                 if (u + 1 + D < R) c[(u + 1 + D) % R] = load_chunk<BITS>(qlane + (size_t)min(r0 + u + 1 + D, g.M - 1) * row_dwords);
             }
-            // One column: the look-ups of row u + 1 are issued one at a time between the products of row u (two
-            // field extractions, one look-up, the products of one look-up) instead of as a block of 16 -- the
-            // workgroups of a launch run in step, and blocks of look-ups from all of them fill the LDS queue while
-            // the vector ALUs idle (22016x8192 fused 22.4 -> 21.2 us, 8192x8192 11.0 -> 10.3 us, 7B shapes 1-2 %).
-            constexpr bool kInterleave = NB == 1;
-            if (!(kInterleave && u + 1 < R)) __builtin_amdgcn_sched_barrier(0);
-            float a[NB];
-            dot_chunk<NB>(w[u & 1], xr, a);
+            // The look-ups of row u + 1 are issued one at a time between the products of row u (two field extractions,
+            // one look-up, the products of one look-up) instead of as a block of 16 -- the workgroups of a launch run in
+            // step, and blocks of look-ups from all of them fill the LDS queue while the vector ALUs idle.
+            acc[u] = dot_chunk(w[u & 1], xr);
+            if (u + 1 < R) {
 #pragma unroll
-            for (int t = 0; t < NB; ++t) acc[t][u] = a[t];
-            if (kInterleave && u + 1 < R) {
-                constexpr int L = 16;                                 // look-ups per row slice and lane
-#pragma unroll
-                for (int p = 0; p < L; ++p) {
+                for (int p = 0; p < 16; ++p) {
                     __builtin_amdgcn_sched_group_barrier(0x2, 2, 0);          // VALU: the offsets of one look-up
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        // DS read
-                    __builtin_amdgcn_sched_group_barrier(0x2, 16 / L, 0);     // VALU: the products of one look-up
+                    __builtin_amdgcn_sched_group_barrier(0x2, 1, 0);          // VALU: the products of one look-up
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        // reduce the R row sums jointly: afterwards lane l holds row (l mod R) summed over its 16-lane row
-#pragma unroll
-        for (int t = 0; t < NB; ++t) {
-            row_block_reduce<R>(acc[t], lane);
-            if ((lane & 15) < R) part[((wave * 4 + (lane >> 4)) * R + (lane & 15)) * NB + t] = acc[t][0];
-        }
+        // reduce the R row sums jointly over each 16-lane row of the wave
+        row_block_reduce<R>(acc, lane);
+        if (row_block_valid(lane) && (R == 8 || !(lane & 8))) part[(wave * 4 + (lane >> 4)) * R + row_block_class<R>(lane)] = acc[0];
         next_batch = UB;                                             // the sparse wave takes batches 0 .. UB-1
     } else {
         // ---- sparse wave(s)
         if (dense) {
             __syncthreads();                                          // the dense waves' table barrier
-            if (sr.nbatch > 2) sparse_round<NB, R, UB>(g, x, sr, rp, 0, 1, lane, myslots);
-            else if (sr.nbatch > 0) sparse_round<NB, R, 2>(g, x, sr, rp, 0, 1, lane, myslots);
+            if (sr.nbatch > 2) sparse_round<R, UB>(g, x, sr, rp, 0, 1, lane, myslots);
+            else if (sr.nbatch > 0) sparse_round<R, 2>(g, x, sr, rp, 0, 1, lane, myslots);
             next_batch = UB;
         }
     }
     // ---- what is left of the sparse term (everything in a sparse-only launch): batch b goes to wave
     //      (b - next_batch) mod NW, UB batches per wave and round
     for (int b0 = next_batch + wave; b0 < sr.nbatch; b0 += NW * UB)   // uniform
-        sparse_round<NB, R, UB>(g, x, sr, rp, b0, NW, lane, myslots);
+        sparse_round<R, UB>(g, x, sr, rp, b0, NW, lane, myslots);
     __syncthreads();
 
     // combine the slice sums and the sparse partial sums in a fixed order, round once
-    uint16_t* __restrict__ y = static_cast<uint16_t*>(g.y) + g.bt0;
-    if (tid < nrows * NB) {
-        const int r = tid / NB, t = tid - r * NB;
-        if (t < bn) {
-            float s = 0.f;
-            for (int w = 0; w < 4 * W; ++w) s += part[(w * R + r) * NB + t];
-            if (sparse)
-                for (int w = 0; w < NW; ++w) s += spart[(w * R + r) * NB + t];
-            const size_t o = (size_t)(r0 + r) * B + t;
-            if (g.accumulate) s += half_bits_to_float(y[o]);
-            y[o] = float_to_half_bits(s);
-        }
+    uint16_t* __restrict__ y = static_cast<uint16_t*>(g.y);
+    if (tid < nrows) {
+        float s = 0.f;
+        for (int w = 0; w < 4 * W; ++w) s += part[w * R + tid];
+        if (sparse)
+            for (int w = 0; w < NW; ++w) s += spart[w * R + tid];
+        if (g.accumulate) s += half_bits_to_float(y[r0 + tid]);
+        y[r0 + tid] = float_to_half_bits(s);
     }
 }
 
@@ -1156,84 +1028,25 @@ __global__ void __launch_bounds__(256) fp16_gemv_kernel(int M, int N, int B, con
         }
 }
 
-// ---------------------------------------------------------------------------------------------- machine probe
-// How far do table look-ups (LDS) and vector-ALU work of different waves overlap on a compute unit?  Every wave runs
-// `iters` iterations of NL random look-ups in a private 64-entry table (the access pattern of the 3-bit pair tables) and
-// NV integer multiply-adds in four independent chains.  Timing (NL, 0), (0, NV) and (NL, NV) with 16 waves per compute
-// unit tells whether the two pipelines add up or hide each other; the answer (they mostly add up) is what bounds the
-// decode of the matvec kernels.
-template <int NL, int NV>
-__global__ void __launch_bounds__(1024) probe_lds_valu_kernel(u32* out, int iters, u32 seed) {
-    __shared__ __align__(16) u32 tab[16 * 64];
-    for (int i = threadIdx.x; i < 16 * 64; i += blockDim.x) tab[i] = (u32)i * 7u + seed;
-    __syncthreads();
-    const char* mytab = reinterpret_cast<const char*>(tab) + (threadIdx.x >> 6) * 256;
-    u32 s = (threadIdx.x + blockIdx.x * 1024u) * 2654435761u + seed;
-    auto next = [&]() { s ^= s << 13; s ^= s >> 17; s ^= s << 5; return s; };
-    next(); next();
-    u32 a[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) a[i] = ((next() >> 9) & 63u) * 4u;
-    u32 acc = 0, v0 = s, v1 = s * 3u, v2 = s * 5u, v3 = s * 7u;
-    for (int it = 0; it < iters; ++it) {
-        const u32 m = ((u32)it & 63u) * 4u;                          // uniform: keeps the lanes' indices a random set
-#pragma unroll
-        for (int i = 0; i < NL; ++i) acc ^= *reinterpret_cast<const u32*>(mytab + (a[i] ^ m));
-#pragma unroll
-        for (int i = 0; i < NV / 4; ++i) {
-            v0 = v0 * 0x9E3779B1u + v3; v1 = v1 * 0x85EBCA6Bu + v0; v2 = v2 * 0xC2B2AE35u + v1; v3 = v3 * 0x27D4EB2Fu + v2;
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    if ((acc ^ v0 ^ v1 ^ v2 ^ v3) == 0x12345u) out[0] = acc;         // keeps the work alive; practically never true
-}
-
-hipError_t launch_probe_lds_valu(int lookups, int mads, int waves_per_cu, int iters, void* out, hipStream_t s) {
-    const dim3 grid(256), block(64 * waves_per_cu);
-    u32* o = static_cast<u32*>(out);
-#define SQ_PROBE(NL_, NV_) if (lookups == NL_ && mads == NV_) { hipLaunchKernelGGL((probe_lds_valu_kernel<NL_, NV_>), grid, block, 0, s, o, iters, 17u); return hipGetLastError(); }
-    SQ_PROBE(16, 0) SQ_PROBE(16, 48) SQ_PROBE(16, 96) SQ_PROBE(16, 128) SQ_PROBE(0, 48) SQ_PROBE(0, 96) SQ_PROBE(0, 128)
-#undef SQ_PROBE
-    return hipErrorInvalidValue;
-}
-
 // ---------------------------------------------------------------------------------------------- launchers
-template <int BITS, int NB, int R, int D>
+template <int BITS, int R, int D>
 static hipError_t launch_matvec_r(const MatvecArgs& g, hipStream_t s) {
     const int W = g.qidx ? (g.N + kSliceCols - 1) / kSliceCols : 0;
     const int S = g.nnz > 0 ? (W ? 1 : kSparseOnlyWaves) : (W ? 0 : 1);
-    const int waves = W + S;
-    const int grid = (g.M + R - 1) / R;
-    // batched kernels hold 32 * NB activations per lane: give them the larger register budget of a block
-    // of at most 512 threads whenever the row is narrow enough
-    if constexpr (NB > 1) {
-        // stage the whole activation slice of a wave at once when the buffers of the block stay within 80 KB (two blocks per compute unit)
-        if ((size_t)W * XStage<NB, 64>::kBytes <= 80 * 1024) {
-            const size_t stage = (size_t)W * XStage<NB, 64>::kBytes;
-            hipLaunchKernelGGL((matvec_kernel<BITS, NB, R, D, 1024, 64>), dim3(grid), dim3(waves * kWave), stage, s, g);
-        } else {
-            const size_t stage = (size_t)W * XStage<NB, 16>::kBytes;
-            hipLaunchKernelGGL((matvec_kernel<BITS, NB, R, D, 1024, 16>), dim3(grid), dim3(waves * kWave), stage, s, g);
-        }
-        return hipGetLastError();
-    }
-    hipLaunchKernelGGL((matvec_kernel<BITS, NB, R, D, 1024, 16>), dim3(grid), dim3(waves * kWave), 0, s, g);
+    hipLaunchKernelGGL((matvec_kernel<BITS, R, D>), dim3((g.M + R - 1) / R), dim3((W + S) * kWave), 0, s, g);
     return hipGetLastError();
 }
 
-template <int BITS, int NB>
-static hipError_t launch_matvec_t(const MatvecArgs& g, hipStream_t s) {
-    // rows per workgroup: the activations of NB batch columns and the index stream in flight share the registers
-    if constexpr (NB == 4) {
-        return launch_matvec_r<BITS, NB, 4, 2>(g, s);
-    } else if constexpr (NB == 2) {
-        return g.rows_per_wg <= 4 ? launch_matvec_r<BITS, NB, 4, 2>(g, s) : launch_matvec_r<BITS, NB, 8, 2>(g, s);
-    } else {
-        if (g.rows_per_wg <= 2) return launch_matvec_r<BITS, NB, 2, 2>(g, s);
-        if (g.rows_per_wg <= 4) return launch_matvec_r<BITS, NB, 4, 2>(g, s);
-        if (g.rows_per_wg <= 8) return launch_matvec_r<BITS, NB, 8, 2>(g, s);
-        return launch_matvec_r<BITS, NB, 16, 4>(g, s);
-    }
+// One activation column.  Rows per workgroup: when all workgroups of the launch are resident at once (at most 8 waves on each of
+// the 1024 SIMDs) 4 rows is the fastest -- the whole matrix is requested within the first microsecond and the time after the
+// last byte arrives is the decode time of one workgroup, which grows with its row count.  Larger launches run in several
+// generations; there 8 rows keep the dense waves busy for as long as the sparse chain of the block (row pointers -> columns /
+// values -> gathers) takes, so the sparse wave does not hold the block's slot.
+template <int BITS>
+static hipError_t launch_matvec_one(const MatvecArgs& g, hipStream_t s) {
+    const int waves = g.qidx ? (g.N + kSliceCols - 1) / kSliceCols + (g.nnz > 0 ? 1 : 0) : kSparseOnlyWaves;
+    const long long resident_waves = 256ll * 4 * 8;
+    return ((long long)(g.M + 3) / 4) * waves <= resident_waves ? launch_matvec_r<BITS, 4, 2>(g, s) : launch_matvec_r<BITS, 8, 2>(g, s);
 }
 
 // up to 16 columns in one launch: 32 rows per workgroup when that still gives every compute unit a workgroup
@@ -1248,12 +1061,9 @@ static hipError_t launch_matvec_b16_r(const MatvecArgs& g, hipStream_t s) {
     const int nwin = g.qidx ? g.N / 128 : 0;
     const int NW = nwin ? (nwin < kB16Waves ? nwin : kB16Waves) : kB16Waves;   // without a dense term all waves share the sparse steps
     const size_t lds = (size_t)R * TableShape<BITS>::kTableDwords * 4 + (size_t)R * (2 << BITS) + (size_t)NW * kB16StageBytes;
-    static bool raised = false;                                      // idempotent: a race only repeats the call
-    if (!raised) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&matvec_b16_kernel<BITS, RG, B4>), hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
+    // raised on every launch: the attribute belongs to the current device's copy of the kernel, and the call is a host-side table update
+    const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(&matvec_b16_kernel<BITS, RG, B4>), hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+    if (ea != hipSuccess) return ea;
     hipLaunchKernelGGL((matvec_b16_kernel<BITS, RG, B4>), dim3((g.M + R - 1) / R), dim3(NW * kWave), lds, s, g);
     return hipGetLastError();
 }
@@ -1275,35 +1085,11 @@ static hipError_t launch_matvec_b16(const MatvecArgs& g, hipStream_t s) {
     return g.M >= kB16TwoGroupsMinM ? launch_matvec_b16_b<BITS, 2>(g, s) : launch_matvec_b16_b<BITS, 1>(g, s);
 }
 
-template <int BITS>
-static hipError_t launch_matvec_b(const MatvecArgs& g0, hipStream_t s) {
-    // Two or more columns: one launch of the 16-column kernel (8192x8192 fused at 2 / 4 columns: 19.0 / 20.4 us against 25.1 /
-    // 22.3 us for a kernel built on the 4x4x4 matrix instruction, which this one replaced); without a dense term from three
-    // columns on (two columns: 10.7 us against 7.3 us for the vector-ALU kernel below).
-    if (g0.mfma_batch && (g0.B >= 3 || (g0.B == 2 && g0.qidx))) {
-        MatvecArgs g = g0;
-        g.bt0 = 0; g.bn = g0.B;
-        return launch_matvec_b16<BITS>(g, s);
-    }
-    // Everything else -- one column, two columns without a dense term, and calls under an explicit rows-per-workgroup
-    // request -- goes to the vector-ALU kernel in windows: 4 (or 2) columns per launch when the batch is even (their
-    // activations must fit in registers) and one column per launch when it is odd (rows of x are then not dword
-    // aligned).  B = 1, 2 and 4 are single launches.
-    const int step = g0.B == 1 ? 1 : ((g0.B & 1) ? 1 : 4);
-    for (int t0 = 0; t0 < g0.B; t0 += step) {
-        MatvecArgs g = g0;
-        g.bt0 = t0; g.bn = min(step, g0.B - t0);
-        hipError_t e;
-        if (g.bn == 1) e = launch_matvec_t<BITS, 1>(g, s);
-        else if (g.bn == 2) e = launch_matvec_t<BITS, 2>(g, s);
-        else e = launch_matvec_t<BITS, 4>(g, s);
-        if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
-}
-
 hipError_t launch_matvec(const MatvecArgs& g, hipStream_t s) {
-    return g.bits == 2 ? launch_matvec_b<2>(g, s) : (g.bits == 3 ? launch_matvec_b<3>(g, s) : launch_matvec_b<4>(g, s));
+    // one column: the vector-ALU kernel; two or more: one launch of the 16-column kernel (every weight is decoded once for all
+    // columns), also without a dense term
+    if (g.B == 1) return g.bits == 2 ? launch_matvec_one<2>(g, s) : (g.bits == 3 ? launch_matvec_one<3>(g, s) : launch_matvec_one<4>(g, s));
+    return g.bits == 2 ? launch_matvec_b16<2>(g, s) : (g.bits == 3 ? launch_matvec_b16<3>(g, s) : launch_matvec_b16<4>(g, s));
 }
 
 hipError_t launch_csr_rowwise(const MatvecArgs& g0, hipStream_t s) {

@@ -8,13 +8,6 @@ import torch
 from . import binding
 
 
-def extraction_counts(M: int, N: int, outlier_frac: float, sens_frac: float):
-    """Sec. 4.2 percentages as counts: half of the outlier share on each tail, the sensitive share on its own."""
-    total = M * N
-    n_tail = int(outlier_frac * total / 2)
-    return n_tail, n_tail, int(sens_frac * total)
-
-
 @dataclass
 class QuantizedLayer:
     M: int

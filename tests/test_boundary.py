@@ -90,16 +90,6 @@ def test_debug_and_baseline_argument_errors():
     expect("SQLLM_ERR_BATCH", sq.sqllm_fp16_gemv, 4, 16, 0, A, A, A)
 
 
-def test_probe_argument_errors():
-    f = sq.sqllm_probe_lds_valu
-    expect("SQLLM_ERR_SHAPE", f, 16, 7, 16, 100, A)
-    expect("SQLLM_ERR_SHAPE", f, 0, 0, 16, 100, A)
-    expect("SQLLM_ERR_SHAPE", f, 16, 48, 17, 100, A)
-    expect("SQLLM_ERR_SHAPE", f, 16, 48, 16, 0, A)
-    expect("SQLLM_ERR_NULL", f, 16, 48, 16, 100, None)
-    expect("SQLLM_ERR_ALIGN", f, 16, 48, 16, 100, A + 2)
-
-
 def test_empty_problem_is_ok_without_a_device():
     # M == 0: nothing to do, nothing is enqueued, no HIP call is made
     sq.sqllm_lut_gemv(0, 128, 3, 1, A, A, A, A, stream=0)
@@ -114,8 +104,6 @@ def test_algorithmic_bytes_and_status_strings():
     assert sq.sqllm_algorithmic_bytes(4096, 4096, 4, 0, 1) == 4096 * 4096 // 2 + 4096 * 32 + 2 * 8192
     L = sq.lib()
     assert L.sqllm_status_string(0) == b"SQLLM_OK" and L.sqllm_status_string(3) == b"SQLLM_ERR_SHAPE"
-    old = sq.sqllm_set_rows_per_workgroup(8)
-    assert sq.sqllm_set_rows_per_workgroup(old) == 8
 
 
 def test_quantize_argument_errors():
@@ -149,5 +137,9 @@ def test_quantize_argument_errors():
     call("SQLLM_ERR_ALIGN", vals=A + 1)
     # nothing to extract: cols / vals may be NULL; M == 0: nothing is enqueued
     f(0, 128, 3, 8, A, A, 0, 0, 0, A, ws, A, A, A, None, None, None, 0)
-    assert sq.extraction_counts(4096, 4096, 0.004, 0.0005) == (33554, 33554, 8388)
-    assert sq.extraction_counts(4096, 4096, 0.0, 0.0) == (0, 0, 0)
+    assert sq.sqllm_extraction_counts(4096, 4096, 0.004, 0.0005) == (33554, 33554, 8388)
+    assert sq.sqllm_extraction_counts(4096, 4096, 0.0, 0.0) == (0, 0, 0)
+    assert sq.sqllm_extraction_counts(11008, 4096, 0.004, 0.0005) == (int(0.004 * 11008 * 4096 / 2),) * 2 + (int(0.0005 * 11008 * 4096),)
+    for bad in ((-1, 128, 0.1, 0.1), (4, 128, -0.1, 0.0), (4, 128, 0.6, 0.5)):
+        with pytest.raises(sq.SqllmError):
+            sq.sqllm_extraction_counts(*bad)

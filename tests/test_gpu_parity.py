@@ -254,16 +254,3 @@ def test_fp16_gemv_baseline():
         sq.sqllm_fp16_gemv(M, N, B, wd, xd, yd)
         y_ref, a_ref = oracle.fp16_matvec(w, x)
         check_y(yd.cpu().numpy().view(np.float16).astype(np.float64), y_ref, a_ref, N, "fp16_gemv")
-
-
-def test_rows_per_workgroup_knob_changes_nothing_observable():
-    import paper_2306_07629_amd as sq
-    L = gen.make_layer(257, 4096, 3, frac=0.0045, skew=(0.1, 0.5), seed=21)
-    D = _dev(L)
-    y_ref, a_ref = oracle.layer_matvec(L)
-    try:
-        for rows in (1, 2, 3, 8, 16, 64):
-            sq.sqllm_set_rows_per_workgroup(rows)
-            check_y(D.matvec().cpu().numpy().view(np.float16).astype(np.float64), y_ref, a_ref, L.N, f"rows={rows}")
-    finally:
-        sq.sqllm_set_rows_per_workgroup(0)

@@ -57,7 +57,7 @@ def test_quantize_matches_the_oracle(M, N, bits, of, sf, max_iter):
     print(f"case M={M} N={N} bits={bits} outliers={of} sensitive={sf} max_iter={max_iter}", flush=True)
     w = gen.make_weights(M, N, 500 + M + N)
     s = gen.make_sens(M, N, 500 + M + N)
-    n_lo, n_hi, n_sens = sq.extraction_counts(M, N, of, sf)
+    n_lo, n_hi, n_sens = sq.sqllm_extraction_counts(M, N, of, sf)
     ref = qo.quantize_layer(w, s, bits, n_lo, n_hi, n_sens, max_iter)
     got = run_gpu(w, s, bits, n_lo, n_hi, n_sens, max_iter)
     compare(M, N, bits, got, ref)
@@ -70,7 +70,7 @@ def test_unweighted_and_degenerate_inputs():
     w = gen.make_weights(M, N, 77)
     ones = np.ones((M, N), dtype=np.uint16)
     # all sensitivities equal: plain k-means (Eq. 1); no weight can be above the sensitivity threshold
-    n_lo, n_hi, _ = sq.extraction_counts(M, N, 0.01, 0.0)
+    n_lo, n_hi, _ = sq.sqllm_extraction_counts(M, N, 0.01, 0.0)
     compare(M, N, bits, run_gpu(w, ones, bits, n_lo, n_hi, 5, 30), qo.quantize_layer(w, ones, bits, n_lo, n_hi, 5, 30))
     # rows of equal weights, of zeros (both signs), and rows whose sensitivities are all zero
     w2 = w.copy()
@@ -95,7 +95,7 @@ def test_full_size_layer_on_sampled_rows():
     M, N, bits = 4096, 4096, 3
     w = gen.make_weights(M, N, 4096)
     s = gen.make_sens(M, N, 4096)
-    n_lo, n_hi, n_sens = sq.extraction_counts(M, N, 0.004, 0.0005)
+    n_lo, n_hi, n_sens = sq.sqllm_extraction_counts(M, N, 0.004, 0.0005)
     rows = np.unique(np.concatenate([[0, 1, M - 1], np.random.default_rng(3).integers(0, M, 45)]))
     ref = qo.quantize_layer(w, s, bits, n_lo, n_hi, n_sens, 40, rows=rows)
     got = run_gpu(w, s, bits, n_lo, n_hi, n_sens, 40)
@@ -115,7 +115,7 @@ def test_quantised_layer_runs_through_the_matvec():
     M, N, bits = 300, 4096, 4
     w = gen.make_weights(M, N, 91)
     s = gen.make_sens(M, N, 91)
-    n_lo, n_hi, n_sens = sq.extraction_counts(M, N, 0.004, 0.0005)
+    n_lo, n_hi, n_sens = sq.sqllm_extraction_counts(M, N, 0.004, 0.0005)
     got = run_gpu(w, s, bits, n_lo, n_hi, n_sens, 30)
     q = got["dev"]
     x = gen.make_x(N, 1, 91)

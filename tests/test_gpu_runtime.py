@@ -91,29 +91,3 @@ def test_guard_regions_around_outputs_stay_untouched(bits, M, N, B):
     assert bool((wbuf[:pad] == SENT).all()) and bool((wbuf[pad + M * N:] == SENT).all())
     assert np.array_equal(idx.view(M, N).cpu().numpy(), oracle.unpack(M, N, bits, L.qidx))
     assert np.array_equal(w.view(M, N).cpu().numpy().view(np.uint16), oracle.dequant(M, N, bits, L.qidx, L.lut))
-
-
-def test_inputs_at_the_very_end_of_an_allocation():
-    """the index stream, tables and CSR arrays end exactly at the end of their allocations (tail lanes and
-    rows are clamped, never read past the end); checked for correctness of the result"""
-    import torch
-    import paper_2306_07629_amd as sq
-    for bits, M, N, B in [(3, 5, 2176, 1), (4, 3, 128, 1), (3, 2, 28672, 1), (2, 5, 2176, 1), (2, 1, 128, 1),
-                          (3, 5, 2176, 16), (4, 19, 128, 5), (2, 33, 256, 8), (3, 17, 384, 3)]:
-        L = gen.make_layer(M, N, bits, frac=0.0045, B=B, seed=60 + M + B)
-        D = sq.DeviceLayer(L)          # torch allocates each array exactly as large as its contents
-        y = _f64(D.matvec())
-        y_ref, absdot = oracle.layer_matvec(L)
-        assert (np.abs(y - y_ref) <= TOL * absdot).all()
-
-
-def test_machine_probe_runs():
-    """the LDS / vector-ALU overlap probe: every built combination launches and finishes"""
-    import torch
-    import paper_2306_07629_amd as sq
-    out = torch.zeros(4, dtype=torch.int32, device="cuda")
-    for lookups, mads in ((16, 0), (0, 48), (16, 48), (16, 128)):
-        sq.sqllm_probe_lds_valu(lookups, mads, 4, 50, out)
-    torch.cuda.synchronize()
-    with pytest.raises(sq.SqllmError):
-        sq.sqllm_probe_lds_valu(16, 5, 4, 50, out)
