@@ -146,6 +146,18 @@ int sqllm_quantize_layer(int M, int N, int bits, int max_iter, const void* w, co
                          long long n_lo, long long n_hi, long long n_sens, void* workspace, long long workspace_bytes,
                          void* qidx, void* lut, int* rowptr, int* cols, void* vals, int* iters, void* stream);
 
+/* The same offline pass for callers that cannot allocate device memory -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: no workspace argument, the 5.2 KB of scratch live in a device array the library
+ * itself holds (one copy on every GPU the library is loaded on, until the process ends).  Arguments, results and errors
+ * as for sqllm_quantize_layer; additionally M * N must not exceed SQLLM_NOALLOC_MAX_WEIGHTS (SQLLM_ERR_SHAPE otherwise).
+ * The call allocates and frees nothing.  All calls on one GPU share that GPU's scratch array (it is cleared by the
+ * call's first kernel): calls that overlap on one GPU -- different streams, different threads -- race and give
+ * undefined results; calls on one stream, or ordered by events, are fine.                                        */
+#define SQLLM_NOALLOC_MAX_WEIGHTS (1ll << 31)
+int sqllm_quantize_layer_noalloc(int M, int N, int bits, int max_iter, const void* w, const void* sens,
+                                 long long n_lo, long long n_hi, long long n_sens,
+                                 void* qidx, void* lut, int* rowptr, int* cols, void* vals, int* iters, void* stream);
+
 /* Bytes the method moves for one matvec (indices + tables + CSR arrays + x + y); used for GB/s figures.  */
 long long sqllm_algorithmic_bytes(int M, int N, int bits, long long nnz, int B);
 

@@ -16,7 +16,7 @@ STATUS_NAMES = ["SQLLM_OK", "SQLLM_ERR_NULL", "SQLLM_ERR_BITS", "SQLLM_ERR_SHAPE
 
 EXPORTS = ["sqllm_lut_gemv", "sqllm_csr_spmv", "sqllm_dense_sparse_matvec", "sqllm_csr_spmv_rowwise",
            "sqllm_unpack_indices", "sqllm_dequantize", "sqllm_fp16_gemv", "sqllm_algorithmic_bytes",
-           "sqllm_quantize_workspace_bytes", "sqllm_quantize_layer", "sqllm_extraction_counts",
+           "sqllm_quantize_workspace_bytes", "sqllm_quantize_layer", "sqllm_quantize_layer_noalloc", "sqllm_extraction_counts",
            "sqllm_last_error_string", "sqllm_status_string", "sqllm_version"]
 
 
@@ -47,6 +47,7 @@ def lib() -> ctypes.CDLL:
         L.sqllm_quantize_workspace_bytes.argtypes = [i32, i32]
         L.sqllm_quantize_workspace_bytes.restype = i64
         L.sqllm_quantize_layer.argtypes = [i32, i32, i32, i32, vp, vp, i64, i64, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp]
+        L.sqllm_quantize_layer_noalloc.argtypes = [i32, i32, i32, i32, vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp]
         L.sqllm_extraction_counts.argtypes = [i32, i32, ctypes.c_double, ctypes.c_double, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.sqllm_last_error_string.restype = ctypes.c_char_p
         L.sqllm_status_string.argtypes = [i32]
@@ -115,6 +116,11 @@ def sqllm_quantize_layer(M, N, bits, max_iter, w, sens, n_lo, n_hi, n_sens, work
                          qidx, lut, rowptr, cols, vals, iters=None, stream=None):
     _check(lib().sqllm_quantize_layer(M, N, bits, max_iter, _ptr(w), _ptr(sens), n_lo, n_hi, n_sens, _ptr(workspace), workspace_bytes,
                                       _ptr(qidx), _ptr(lut), _ptr(rowptr), _ptr(cols), _ptr(vals), _ptr(iters), _stream(stream)))
+
+
+def sqllm_quantize_layer_noalloc(M, N, bits, max_iter, w, sens, n_lo, n_hi, n_sens, qidx, lut, rowptr, cols, vals, iters=None, stream=None):
+    _check(lib().sqllm_quantize_layer_noalloc(M, N, bits, max_iter, _ptr(w), _ptr(sens), n_lo, n_hi, n_sens,
+                                              _ptr(qidx), _ptr(lut), _ptr(rowptr), _ptr(cols), _ptr(vals), _ptr(iters), _stream(stream)))
 
 
 def sqllm_algorithmic_bytes(M, N, bits, nnz, B) -> int:

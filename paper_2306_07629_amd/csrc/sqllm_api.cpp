@@ -197,7 +197,7 @@ long long sqllm_quantize_workspace_bytes(int M, int N) {
 
 namespace {
 int run_quantize(int M, int N, int bits, int max_iter, const void* w, const void* sens, long long n_lo, long long n_hi, long long n_sens,
-                 void* workspace, void* qidx, void* lut, int* rowptr, int* cols, void* vals, int* iters, void* stream) {
+                 void* workspace, bool own_scratch, void* qidx, void* lut, int* rowptr, int* cols, void* vals, int* iters, void* stream) {
     int st;
     if ((st = check_bits(bits)) || (st = check_shape(M, N, 1))) return st;
     if (M == 0) return SQLLM_OK;
@@ -206,12 +206,16 @@ int run_quantize(int M, int N, int bits, int max_iter, const void* w, const void
     if (max_iter < 0) return fail(SQLLM_ERR_SHAPE, "max_iter = %d is negative", max_iter);
     if (n_lo < 0 || n_hi < 0 || n_sens < 0 || n_lo >= total || n_hi >= total || n_sens >= total || n_lo + n_hi + n_sens >= (1ll << 31))
         return fail(SQLLM_ERR_NNZ, "extraction counts (%lld, %lld, %lld) out of range for %lld weights", n_lo, n_hi, n_sens, total);
-    if (!w || !sens || !workspace || !qidx || !lut || !rowptr) return fail(SQLLM_ERR_NULL, "a required pointer is NULL");
+    if (!w || !sens || (!own_scratch && !workspace) || !qidx || !lut || !rowptr) return fail(SQLLM_ERR_NULL, "a required pointer is NULL");
     if (n_lo + n_hi + n_sens > 0 && (!cols || !vals)) return fail(SQLLM_ERR_NULL, "cols / vals are NULL although entries may be extracted");
     if (((uintptr_t)w | (uintptr_t)sens | (uintptr_t)qidx | (uintptr_t)lut) & 15) return fail(SQLLM_ERR_ALIGN, "w, sens, qidx and lut must be 16-byte aligned");
     if (((uintptr_t)workspace | (uintptr_t)rowptr | (uintptr_t)cols | (uintptr_t)iters) & 3) return fail(SQLLM_ERR_ALIGN, "workspace, rowptr, cols and iters must be 4-byte aligned");
     if ((uintptr_t)vals & 1) return fail(SQLLM_ERR_ALIGN, "vals must be 2-byte aligned");
     if ((st = check_device())) return st;
+    if (own_scratch) {
+        const hipError_t e = sqllm::quantize_static_scratch(&workspace);
+        if (e != hipSuccess) return hip_fail(e, "address of the library's scratch array");
+    }
     sqllm::QuantArgs a;
     memset(&a, 0, sizeof a);
     a.M = M; a.N = N; a.bits = bits; a.max_iter = max_iter; a.n_lo = n_lo; a.n_hi = n_hi; a.n_sens = n_sens;
@@ -227,7 +231,15 @@ int sqllm_quantize_layer(int M, int N, int bits, int max_iter, const void* w, co
                          void* qidx, void* lut, int* rowptr, int* cols, void* vals, int* iters, void* stream) {
     if (M != 0 && workspace && workspace_bytes < (long long)sqllm::quantize_workspace_bytes())
         return fail(SQLLM_ERR_SHAPE, "workspace of %lld bytes, %lld needed", workspace_bytes, (long long)sqllm::quantize_workspace_bytes());
-    return run_quantize(M, N, bits, max_iter, w, sens, n_lo, n_hi, n_sens, workspace, qidx, lut, rowptr, cols, vals, iters, stream);
+    return run_quantize(M, N, bits, max_iter, w, sens, n_lo, n_hi, n_sens, workspace, false, qidx, lut, rowptr, cols, vals, iters, stream);
+}
+
+int sqllm_quantize_layer_noalloc(int M, int N, int bits, int max_iter, const void* w, const void* sens,
+                                 long long n_lo, long long n_hi, long long n_sens,
+                                 void* qidx, void* lut, int* rowptr, int* cols, void* vals, int* iters, void* stream) {
+    if ((long long)M * N > SQLLM_NOALLOC_MAX_WEIGHTS)
+        return fail(SQLLM_ERR_SHAPE, "M * N = %lld exceeds SQLLM_NOALLOC_MAX_WEIGHTS = %lld", (long long)M * N, (long long)SQLLM_NOALLOC_MAX_WEIGHTS);
+    return run_quantize(M, N, bits, max_iter, w, sens, n_lo, n_hi, n_sens, nullptr, true, qidx, lut, rowptr, cols, vals, iters, stream);
 }
 
 int sqllm_extraction_counts(int M, int N, double outlier_frac, double sens_frac, long long* n_lo, long long* n_hi, long long* n_sens) {

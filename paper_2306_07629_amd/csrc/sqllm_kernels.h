@@ -33,6 +33,7 @@ struct QuantArgs {
     int* iters;             // out, optional: [M]
 };
 size_t quantize_workspace_bytes();
+hipError_t quantize_static_scratch(void** device_ptr);   // the library's own workspace on the current device (no allocation)
 hipError_t launch_quantize(const QuantArgs& a, hipStream_t s);
 
 hipError_t launch_matvec(const MatvecArgs& g, hipStream_t s);

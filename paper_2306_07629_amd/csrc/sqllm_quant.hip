@@ -15,6 +15,7 @@
 //   4. fp16 tables, final indices (nearest table entry in exact arithmetic, ties to the lower index; an extracted
 //      position gets the entry nearest to zero) and the packed index stream in the layout the matvec reads.
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stdint.h>
 
 #include "sqllm_kernels.h"
@@ -520,6 +521,28 @@ __global__ void __launch_bounds__(T) quant_kmeans_kernel(int M, int N, int NP, i
 
 // ---------------------------------------------------------------------------------------------- launcher
 size_t quantize_workspace_bytes() { return (size_t)kWsWords * 4; }
+
+// Scratch of the entry point that allocates nothing: the same 5.2 KB workspace, held by the library itself in device memory
+// of every GPU the code object is loaded on.  In host code the array's name only stands for the symbol; its device address
+// is asked for once per device (with that device current) and remembered.
+static __device__ __align__(256) u32 scratch[kWsWords];
+
+hipError_t quantize_static_scratch(void** out) {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> ptrs[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    void* p = dev >= 0 && dev < kMaxDevices ? ptrs[dev].load(std::memory_order_acquire) : nullptr;
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        if (dev >= 0 && dev < kMaxDevices) ptrs[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return hipSuccess;
+}
 
 hipError_t launch_quantize(const QuantArgs& a, hipStream_t s) {
     u32* ws = static_cast<u32*>(a.workspace);
