@@ -151,6 +151,10 @@ DECODE_STEP = {
     "llama7b_decode_step_4bit": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 4, 0.0045, (0.10, 0.50)),
     # projections that share an input stacked row-wise (q,k,v -> 12288 rows; gate,up -> 22016 rows): 128 launches
     "llama7b_decode_step_3bit_stacked": (32, [(12288, 4096), (4096, 4096), (22016, 4096), (4096, 11008)], 3, 0.0045, (0.10, 0.50)),
+    # the same 224 layers through sqllm_dense_sparse_matvec_multi: one call (= one launch) per decoder block, or one call for
+    # the whole step (launches of eight layers).  The matvecs of the synthetic step do not depend on each other.
+    "llama7b_decode_step_3bit_multi_block": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 3, 0.0045, (0.10, 0.50)),
+    "llama7b_decode_step_3bit_multi_step": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 3, 0.0045, (0.10, 0.50)),
 }
 
 
@@ -186,9 +190,32 @@ def bench_decode_step(args):
     torch.cuda.synchronize()
     n_layers = len(dev)
 
-    def step(_s):
+    multi = "multi_block" if args.workload.endswith("_multi_block") else ("multi_step" if args.workload.endswith("_multi_step") else None)
+    if multi:
+        per_call = len(shapes) if multi == "multi_block" else n_layers
+        calls = [sq.layer_descriptors([D.descriptor() for D in dev[i:i + per_call]]) for i in range(0, n_layers, per_call)]
+        # the multi-layer call must reproduce the bits of the single-layer entry point (itself checked against the oracle above)
         for D in dev:
             D.matvec()
+        torch.cuda.synchronize()
+        want = [D.y.clone() for D in dev]
+        for D in dev:
+            D.y.zero_()
+        for c in calls:
+            sq.sqllm_dense_sparse_matvec_multi(c)
+        torch.cuda.synchronize()
+        if not all(torch.equal(D.y, w) for D, w in zip(dev, want)):
+            print("bench.py: the multi-layer call does not reproduce the single-layer results", file=sys.stderr)
+            sys.exit(4)
+        del want
+
+        def step(_s):
+            for c in calls:
+                sq.sqllm_dense_sparse_matvec_multi(c)
+    else:
+        def step(_s):
+            for D in dev:
+                D.matvec()
 
     G = not args.no_graph
     sec, wall = time_steps(torch, step, args.steps, args.warmup, G, args.replays, tag="cold")
@@ -231,7 +258,9 @@ def bench_decode_step(args):
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "blocks": blocks, "layers_per_block": [f"{M}x{N}" for M, N in shapes], "bits": bits, "sparse_frac": frac,
                    "skew": skew, "batch": 1, "seed": SEED, "distinct_layers_resident": n_layers, "resident_gb": step_bytes / 1e9,
-                   "parity_checked_blocks": checked, "matvecs_per_step": n_layers},
+                   "parity_checked_blocks": checked, "matvecs_per_step": n_layers,
+                   "entry_point": "sqllm_dense_sparse_matvec_multi, one call per " + ("decoder block" if multi == "multi_block" else "step") if multi else "sqllm_dense_sparse_matvec, one call per layer"},
+        "replay_stats_ms_for_K_steps": REPLAY_STATS.get("cold"),
         "us_per_matvec": us_step / n_layers, "effective_gbs": gbs, "pct_of_hbm_roofline": 100.0 * gbs / HBM_PEAK_GBS,
         "fp16_step_us": {"own_kernel": us_own, "torch_mv": us_torch}, "speedup_vs_fp16": min(us_own, us_torch) / us_step,
         "parity_worst_err_over_bound": worst, "launch_mode": "hip_graph_replay" if G else "python_ctypes", "host_wall_s_timed_region": wall,

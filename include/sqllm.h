@@ -100,6 +100,32 @@ int sqllm_dense_sparse_matvec(int M, int N, int bits, long long nnz, int B,
                               const int* rowptr, const int* cols, const void* vals,
                               const void* x, void* y, void* stream);
 
+/* Several independent layers, one activation vector each (the per-token stack of matvecs of Sec. 4.3, last paragraph: q, k, v of
+ * a decoder block share an input and do not depend on each other, gate and up likewise), in as few kernel launches as possible.
+ *   layers   HOST pointer to `count` descriptors; every pointer inside a descriptor is a device pointer with the meaning,
+ *            layout and alignment of the argument of the same name of sqllm_dense_sparse_matvec (B = 1).  All layers of one
+ *            call have the same `bits`.  The descriptors are copied into the kernel arguments: the array may be reused or
+ *            freed as soon as the call returns.
+ * Consecutive layers are merged into launches of up to SQLLM_MAX_LAYERS_PER_LAUNCH layers (a launch ends early where the row
+ * width changes between "below 16384" and "16384 and wider", because the two classes run with different rows per workgroup).
+ * Each y is bit for bit what a separate sqllm_dense_sparse_matvec call gives; what is saved is the launch gap and the ramp-up
+ * and tail of every layer but the last.  The layers of one call must not depend on each other and their y must not overlap.
+ * Errors as for sqllm_dense_sparse_matvec, reported for the first offending layer; nothing is enqueued if any layer fails
+ * validation.  count == 0 -> SQLLM_OK.                                                                                          */
+typedef struct {
+    int M, N, bits;
+    long long nnz;
+    const void* qidx;
+    const void* lut;
+    const int* rowptr;
+    const int* cols;
+    const void* vals;
+    const void* x;
+    void* y;
+} sqllm_layer;
+#define SQLLM_MAX_LAYERS_PER_LAUNCH 8
+int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* stream);
+
 /* One thread per row over the CSR matrix — the "standard" kernel the paper's App. C compares the balanced
  * one against.  Same arguments and result as sqllm_csr_spmv; kept as the ablation baseline.              */
 int sqllm_csr_spmv_rowwise(int M, int N, long long nnz, int B,

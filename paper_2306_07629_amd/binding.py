@@ -14,10 +14,17 @@ OK = 0
 STATUS_NAMES = ["SQLLM_OK", "SQLLM_ERR_NULL", "SQLLM_ERR_BITS", "SQLLM_ERR_SHAPE", "SQLLM_ERR_ALIGN", "SQLLM_ERR_NNZ",
                 "SQLLM_ERR_BATCH", "SQLLM_ERR_HIP", "SQLLM_ERR_DEVICE"]
 
-EXPORTS = ["sqllm_lut_gemv", "sqllm_csr_spmv", "sqllm_dense_sparse_matvec", "sqllm_csr_spmv_rowwise",
+EXPORTS = ["sqllm_lut_gemv", "sqllm_csr_spmv", "sqllm_dense_sparse_matvec", "sqllm_dense_sparse_matvec_multi", "sqllm_csr_spmv_rowwise",
            "sqllm_unpack_indices", "sqllm_dequantize", "sqllm_fp16_gemv", "sqllm_algorithmic_bytes",
            "sqllm_quantize_workspace_bytes", "sqllm_quantize_layer", "sqllm_quantize_layer_noalloc", "sqllm_extraction_counts",
            "sqllm_last_error_string", "sqllm_status_string", "sqllm_version"]
+
+
+class LayerDesc(ctypes.Structure):
+    """sqllm_layer of include/sqllm.h"""
+    _fields_ = [("M", ctypes.c_int), ("N", ctypes.c_int), ("bits", ctypes.c_int), ("nnz", ctypes.c_longlong),
+                ("qidx", ctypes.c_void_p), ("lut", ctypes.c_void_p), ("rowptr", ctypes.c_void_p), ("cols", ctypes.c_void_p),
+                ("vals", ctypes.c_void_p), ("x", ctypes.c_void_p), ("y", ctypes.c_void_p)]
 
 
 class SqllmError(RuntimeError):
@@ -39,6 +46,7 @@ def lib() -> ctypes.CDLL:
         L.sqllm_csr_spmv.argtypes = [i32, i32, i64, i32, vp, vp, vp, vp, vp, i32, vp]
         L.sqllm_csr_spmv_rowwise.argtypes = [i32, i32, i64, i32, vp, vp, vp, vp, vp, i32, vp]
         L.sqllm_dense_sparse_matvec.argtypes = [i32, i32, i32, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.sqllm_dense_sparse_matvec_multi.argtypes = [i32, ctypes.POINTER(LayerDesc), vp]
         L.sqllm_unpack_indices.argtypes = [i32, i32, i32, vp, vp, vp]
         L.sqllm_dequantize.argtypes = [i32, i32, i32, vp, vp, vp, vp]
         L.sqllm_fp16_gemv.argtypes = [i32, i32, i32, vp, vp, vp, vp]
@@ -94,6 +102,27 @@ def sqllm_csr_spmv_rowwise(M, N, nnz, B, rowptr, cols, vals, x, y, accumulate=0,
 def sqllm_dense_sparse_matvec(M, N, bits, nnz, B, qidx, lut, rowptr, cols, vals, x, y, stream=None):
     _check(lib().sqllm_dense_sparse_matvec(M, N, bits, nnz, B, _ptr(qidx), _ptr(lut), _ptr(rowptr), _ptr(cols), _ptr(vals),
                                            _ptr(x), _ptr(y), _stream(stream)))
+
+
+def _addr(t):
+    if t is None:
+        return None
+    return t if isinstance(t, int) else t.data_ptr()
+
+
+def layer_descriptors(layers):
+    """ctypes array of sqllm_layer from (M, N, bits, nnz, qidx, lut, rowptr, cols, vals, x, y) tuples (tensors or raw addresses)"""
+    arr = (LayerDesc * len(layers))()
+    for d, (M, N, bits, nnz, qidx, lut, rowptr, cols, vals, x, y) in zip(arr, layers):
+        d.M, d.N, d.bits, d.nnz = M, N, bits, nnz
+        d.qidx, d.lut, d.rowptr, d.cols, d.vals, d.x, d.y = (_addr(t) for t in (qidx, lut, rowptr, cols, vals, x, y))
+    return arr
+
+
+def sqllm_dense_sparse_matvec_multi(layers, stream=None):
+    """layers: a ctypes array from layer_descriptors(), or the list of tuples it takes"""
+    arr = layers if isinstance(layers, ctypes.Array) else layer_descriptors(layers)
+    _check(lib().sqllm_dense_sparse_matvec_multi(len(arr), arr, _stream(stream)))
 
 
 def sqllm_unpack_indices(M, N, bits, qidx, idx_out, stream=None):

@@ -130,6 +130,47 @@ int sqllm_dense_sparse_matvec(int M, int N, int bits, long long nnz, int B, cons
     return run_matvec(M, N, bits, nnz, B, qidx, lut, rowptr, cols, vals, x, y, 0, stream);
 }
 
+int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* stream) {
+    static_assert(SQLLM_MAX_LAYERS_PER_LAUNCH == sqllm::kMaxLayersPerLaunch, "header and kernels disagree");
+    if (count < 0) return fail(SQLLM_ERR_SHAPE, "count = %d is negative", count);
+    if (count == 0) return SQLLM_OK;
+    if (!layers) return fail(SQLLM_ERR_NULL, "layers must not be NULL");
+    int st;
+    for (int l = 0; l < count; ++l) {
+        const sqllm_layer& L = layers[l];
+        if ((st = check_bits(L.bits)) || (st = check_shape(L.M, L.N, 1)) || (st = check_dense_ptrs(L.qidx, L.lut)) ||
+            (st = check_sparse(L.nnz, L.rowptr, L.cols, L.vals)) || (st = check_xy(L.x, L.y))) {
+            char msg[200];
+            snprintf(msg, sizeof msg, "%s", g_err);
+            return fail(st, "layer %d: %s", l, msg);
+        }
+        if (L.bits != layers[0].bits) return fail(SQLLM_ERR_BITS, "layer %d: bits = %d, layer 0 has %d (one width per call)", l, L.bits, layers[0].bits);
+    }
+    bool any = false;
+    for (int l = 0; l < count; ++l) any = any || layers[l].M > 0;
+    if (!any) return SQLLM_OK;
+    if ((st = check_device())) return st;
+    int l = 0;
+    while (l < count) {
+        sqllm::MultiArgs m;
+        memset(&m, 0, sizeof m);
+        const int cls = sqllm::multi_rows_per_workgroup(layers[l].N);
+        while (l < count && m.count < sqllm::kMaxLayersPerLaunch && sqllm::multi_rows_per_workgroup(layers[l].N) == cls) {
+            const sqllm_layer& L = layers[l];
+            if (L.M > 0) {
+                const int k = m.count++;
+                m.M[k] = L.M; m.N[k] = L.N; m.nnz[k] = L.nnz; m.qidx[k] = L.qidx; m.lut[k] = L.lut; m.rowptr[k] = L.rowptr; m.cols[k] = L.cols;
+                m.vals[k] = L.vals; m.x[k] = L.x; m.y[k] = L.y;
+            }
+            ++l;
+        }
+        if (m.count == 0) continue;
+        const hipError_t e = sqllm::launch_matvec_multi(m, layers[0].bits, static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return hip_fail(e, "multi-layer matvec launch");
+    }
+    return SQLLM_OK;
+}
+
 int sqllm_csr_spmv_rowwise(int M, int N, long long nnz, int B, const int* rowptr, const int* cols, const void* vals,
                            const void* x, void* y, int accumulate, void* stream) {
     int st;

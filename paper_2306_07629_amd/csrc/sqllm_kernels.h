@@ -18,6 +18,24 @@ struct MatvecArgs {
     void* y;
 };
 
+// Several independent one-column layers in one launch (passed by value as kernel arguments)
+constexpr int kMaxLayersPerLaunch = 8;
+struct MultiArgs {
+    int count;
+    int first_block[kMaxLayersPerLaunch + 1];   // filled by the launcher: workgroups of layer l are first_block[l] .. first_block[l + 1] - 1
+    int M[kMaxLayersPerLaunch], N[kMaxLayersPerLaunch];
+    long long nnz[kMaxLayersPerLaunch];
+    const void* qidx[kMaxLayersPerLaunch];
+    const void* lut[kMaxLayersPerLaunch];
+    const int* rowptr[kMaxLayersPerLaunch];
+    const int* cols[kMaxLayersPerLaunch];
+    const void* vals[kMaxLayersPerLaunch];
+    const void* x[kMaxLayersPerLaunch];
+    void* y[kMaxLayersPerLaunch];
+};
+int multi_rows_per_workgroup(int N);             // rows per workgroup of the one-column kernel for rows of N columns (4 or 8)
+hipError_t launch_matvec_multi(MultiArgs& m, int bits, hipStream_t s);
+
 // Offline side (sqllm_quant.hip): everything is a caller-owned device pointer.
 struct QuantArgs {
     int M, N, bits, max_iter;

@@ -230,6 +230,8 @@ __device__ __forceinline__ int row_block_class(int lane) { return (C == 8 && (la
 // (which the dense decode of the same wave overlaps).  Products are combined per row inside the wave (plain
 // DPP reduction when a batch lies in one row, segmented DPP scan otherwise) and only the last lane of a row
 // segment adds to the wave's private LDS slot of that row: no floating-point atomics, fixed summation order.
+// (One LDS float add per nonzero instead of the scan was measured: lanes meeting in a slot are served one after the other,
+// 22016x8192 fused 19.4 -> 24.9 us.)
 template <int UB>
 struct SparseRegs {
     int c[UB];
@@ -341,8 +343,10 @@ __device__ __forceinline__ void load_row_pointers(const MatvecArgs& g, int r0, i
     sr.P0 = rp[0]; sr.P1 = rp[R]; sr.nbatch = (sr.P1 - sr.P0 + kWave - 1) / kWave;
 }
 
+// The work of one workgroup: rows [R block, R block + R) of layer g, carried by the workgroup's first NW waves
+// (W dense waves, then the sparse wave).
 template <int BITS, int R, int D>
-__global__ void __launch_bounds__(1024) matvec_kernel(MatvecArgs g) {
+__device__ __forceinline__ void matvec_block(const MatvecArgs& g, int block, int NW) {
     static_assert(D >= 2 && D <= R && (R == 4 || R == 8), "prefetch depth, rows per workgroup");
     constexpr int E = TableShape<BITS>::kEntries, K = 1 << BITS;
     constexpr int kRawUnit = TableShape<BITS>::kRawUnit;             // bytes of fp16 tables one lane fetches (16, or 8 for b = 2)
@@ -354,10 +358,9 @@ __global__ void __launch_bounds__(1024) matvec_kernel(MatvecArgs g) {
     __shared__ float spart[(kMaxDenseWaves + 1) * R];                // sparse: [wave][r]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
-    const int NW = blockDim.x >> 6;
     const bool dense = g.qidx != nullptr, sparse = g.nnz > 0;
     const int W = dense ? (g.N + kSliceCols - 1) / kSliceCols : 0;
-    const int r0 = blockIdx.x * R;
+    const int r0 = block * R;
     const int nrows = min(R, g.M - r0);
     const uint16_t* __restrict__ x = static_cast<const uint16_t*>(g.x);
 
@@ -443,9 +446,24 @@ __global__ void __launch_bounds__(1024) matvec_kernel(MatvecArgs g) {
     } else {
         // ---- sparse wave(s)
         if (dense) {
-            __syncthreads();                                          // the dense waves' table barrier
-            if (sr.nbatch > 2) sparse_round<R, UB>(g, x, sr, rp, 0, 1, lane, myslots);
-            else if (sr.nbatch > 0) sparse_round<R, 2>(g, x, sr, rp, 0, 1, lane, myslots);
+            // columns and values of the first batches are requested BEFORE the dense waves' table barrier: the row pointers arrive
+            // together with the fp16 tables, so the second hop of the chain (row pointers -> columns / values -> gathers -> scan)
+            // runs while the tables are built instead of after (22016x8192 fused 21.3 -> 20.5 us)
+            if (sr.nbatch > 2) {
+                SparseRegs<UB> q;
+                sparse_issue_cols_vals<UB>(g, sr, 0, 1, lane, q);
+                __syncthreads();
+                sparse_issue_gathers<UB>(x, q);
+                sparse_reduce<R, UB>(sr, rp, 0, 1, lane, q, myslots);
+            } else if (sr.nbatch > 0) {
+                SparseRegs<2> q;
+                sparse_issue_cols_vals<2>(g, sr, 0, 1, lane, q);
+                __syncthreads();
+                sparse_issue_gathers<2>(x, q);
+                sparse_reduce<R, 2>(sr, rp, 0, 1, lane, q, myslots);
+            } else {
+                __syncthreads();
+            }
             next_batch = UB;
         }
     }
@@ -465,6 +483,30 @@ __global__ void __launch_bounds__(1024) matvec_kernel(MatvecArgs g) {
         if (g.accumulate) s += half_bits_to_float(y[r0 + tid]);
         y[r0 + tid] = float_to_half_bits(s);
     }
+}
+
+template <int BITS, int R, int D>
+__global__ void __launch_bounds__(1024) matvec_kernel(MatvecArgs g) {
+    matvec_block<BITS, R, D>(g, blockIdx.x, blockDim.x >> 6);
+}
+
+// Several independent layers in ONE launch (one activation column each): the grid is the concatenation of the layers' grids,
+// workgroup b belongs to the layer l with first_block[l] <= b < first_block[l + 1].  The launch has as many waves per workgroup
+// as its widest layer needs; in a narrower layer the surplus waves leave at once (a finished wave no longer takes part in the
+// workgroup's barriers).  Every layer is computed by the same code, in the same order of operations, as in a launch of its own,
+// so the results are bit for bit those of separate calls -- what is saved is the launch and the ramp between them: the last
+// workgroups of a layer run beside the first of the next.
+template <int BITS, int R, int D>
+__global__ void __launch_bounds__(1024) matvec_multi_kernel(MultiArgs m) {
+    int l = 0;
+#pragma unroll
+    for (int k = 1; k < kMaxLayersPerLaunch; ++k) l += (k < m.count && (int)blockIdx.x >= m.first_block[k]) ? 1 : 0;   // uniform
+    MatvecArgs g;
+    g.M = m.M[l]; g.N = m.N[l]; g.bits = BITS; g.B = 1; g.bt0 = 0; g.bn = 1; g.accumulate = 0; g.nnz = m.nnz[l];
+    g.qidx = m.qidx[l]; g.lut = m.lut[l]; g.rowptr = m.rowptr[l]; g.cols = m.cols[l]; g.vals = m.vals[l]; g.x = m.x[l]; g.y = m.y[l];
+    const int NW = (g.N + kSliceCols - 1) / kSliceCols + (g.nnz > 0 ? 1 : 0);
+    if ((int)(threadIdx.x >> 6) >= NW) return;
+    matvec_block<BITS, R, D>(g, (int)blockIdx.x - m.first_block[l], NW);
 }
 
 // ---------------------------------------------------------------------------------------------- up to sixteen activation columns on the matrix cores
@@ -1037,16 +1079,35 @@ static hipError_t launch_matvec_r(const MatvecArgs& g, hipStream_t s) {
     return hipGetLastError();
 }
 
-// One activation column.  Rows per workgroup: when all workgroups of the launch are resident at once (at most 8 waves on each of
-// the 1024 SIMDs) 4 rows is the fastest -- the whole matrix is requested within the first microsecond and the time after the
-// last byte arrives is the decode time of one workgroup, which grows with its row count.  Larger launches run in several
-// generations; there 8 rows keep the dense waves busy for as long as the sparse chain of the block (row pointers -> columns /
-// values -> gathers) takes, so the sparse wave does not hold the block's slot.
+// One activation column.  Rows per workgroup, measured (fused, 0.45 % sparse): 4 rows win on 22016x8192 (19.3 against 19.4 us),
+// 8192x8192 (11.0 against 13.4) and 11008x4096 (8.8 against 9.8); rows of eight or more slices -- 8192x22016 with its 11 waves per
+// workgroup, of which a compute unit holds only two -- want 8 rows (25.1 against 27.3 us): the fixed cost of a workgroup (tables,
+// barriers, the final combination) is then spread over twice the stream.
 template <int BITS>
 static hipError_t launch_matvec_one(const MatvecArgs& g, hipStream_t s) {
-    const int waves = g.qidx ? (g.N + kSliceCols - 1) / kSliceCols + (g.nnz > 0 ? 1 : 0) : kSparseOnlyWaves;
-    const long long resident_waves = 256ll * 4 * 8;
-    return ((long long)(g.M + 3) / 4) * waves <= resident_waves ? launch_matvec_r<BITS, 4, 2>(g, s) : launch_matvec_r<BITS, 8, 2>(g, s);
+    return g.qidx && multi_rows_per_workgroup(g.N) == 8 ? launch_matvec_r<BITS, 8, 2>(g, s) : launch_matvec_r<BITS, 4, 2>(g, s);
+}
+
+template <int BITS, int R>
+static hipError_t launch_multi_r(MultiArgs& m, hipStream_t s) {
+    int total = 0, waves = 1;
+    for (int l = 0; l < m.count; ++l) {
+        m.first_block[l] = total;
+        total += (m.M[l] + R - 1) / R;
+        waves = max(waves, (m.N[l] + kSliceCols - 1) / kSliceCols + (m.nnz[l] > 0 ? 1 : 0));
+    }
+    for (int l = m.count; l <= kMaxLayersPerLaunch; ++l) m.first_block[l] = total;
+    if (total == 0) return hipSuccess;
+    hipLaunchKernelGGL((matvec_multi_kernel<BITS, R, 2>), dim3(total), dim3(waves * kWave), 0, s, m);
+    return hipGetLastError();
+}
+
+int multi_rows_per_workgroup(int N) { return (N + kSliceCols - 1) / kSliceCols >= 8 ? 8 : 4; }
+
+hipError_t launch_matvec_multi(MultiArgs& m, int bits, hipStream_t s) {
+    const int R = multi_rows_per_workgroup(m.N[0]);                 // the caller groups layers of one class into a launch
+    if (R == 8) return bits == 2 ? launch_multi_r<2, 8>(m, s) : (bits == 3 ? launch_multi_r<3, 8>(m, s) : launch_multi_r<4, 8>(m, s));
+    return bits == 2 ? launch_multi_r<2, 4>(m, s) : (bits == 3 ? launch_multi_r<3, 4>(m, s) : launch_multi_r<4, 4>(m, s));
 }
 
 // up to 16 columns in one launch: 32 rows per workgroup when that still gives every compute unit a workgroup

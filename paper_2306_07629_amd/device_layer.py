@@ -40,6 +40,10 @@ class DeviceLayer:
                                      self.cols, self.vals, self.x, self.y, stream)
         return self.y
 
+    def descriptor(self):
+        """the tuple binding.layer_descriptors() takes (one activation column)"""
+        return (self.M, self.N, self.bits, self.nnz, self.qidx, self.lut, self.rowptr, self.cols, self.vals, self.x, self.y)
+
     def lut_gemv(self, accumulate=0, stream=None):
         _b.sqllm_lut_gemv(self.M, self.N, self.bits, self.B, self.qidx, self.lut, self.x, self.y, accumulate, stream)
         return self.y

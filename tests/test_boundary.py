@@ -79,6 +79,28 @@ def test_sparse_argument_errors():
     expect("SQLLM_ERR_NNZ", h, 4, 128, -1, 1, A, A, A, A, A)
 
 
+def test_multi_layer_argument_errors():
+    ok = (4, 128, 3, 5, A, A, A, A, A, A, A)
+    f = lambda layers: sq.sqllm_dense_sparse_matvec_multi(layers, stream=0)
+    with pytest.raises(sq.SqllmError) as e:
+        f([ok, (4, 100, 3, 5, A, A, A, A, A, A, A)])
+    assert binding.STATUS_NAMES[e.value.status] == "SQLLM_ERR_SHAPE" and "layer 1" in str(e.value)
+    with pytest.raises(sq.SqllmError) as e:
+        f([ok, ok, (4, 128, 4, 5, A, A, A, A, A, A, A)])
+    assert binding.STATUS_NAMES[e.value.status] == "SQLLM_ERR_BITS" and "layer 2" in str(e.value)
+    with pytest.raises(sq.SqllmError) as e:
+        f([(4, 128, 3, 5, A, A, None, A, A, A, A)])
+    assert binding.STATUS_NAMES[e.value.status] == "SQLLM_ERR_NULL" and "layer 0" in str(e.value)
+    with pytest.raises(sq.SqllmError) as e:
+        f([(4, 128, 3, 0, A, A, None, None, None, A + 2, A)])
+    assert binding.STATUS_NAMES[e.value.status] == "SQLLM_ERR_ALIGN"
+    L = sq.lib()
+    assert L.sqllm_dense_sparse_matvec_multi(-1, None, None) == binding.STATUS_NAMES.index("SQLLM_ERR_SHAPE")
+    assert L.sqllm_dense_sparse_matvec_multi(3, None, None) == binding.STATUS_NAMES.index("SQLLM_ERR_NULL")
+    assert L.sqllm_dense_sparse_matvec_multi(0, None, None) == 0
+    f([(0, 128, 3, 0, A, A, None, None, None, A, A)] * 3)          # only empty layers: nothing is enqueued, no HIP call
+
+
 def test_debug_and_baseline_argument_errors():
     expect("SQLLM_ERR_NULL", sq.sqllm_unpack_indices, 4, 128, 3, A, None)
     expect("SQLLM_ERR_BITS", sq.sqllm_unpack_indices, 4, 128, 1, A, A)

@@ -55,7 +55,7 @@ def one_column_kernel_reads(M, N, bits, rowptr, R):
         P0, P1 = rp[0], rp[R]
         nbatch = (P1 - P0 + WAVE - 1) // WAVE
         if nbatch > 0:
-            NW, UB = W + 1, 8
+            NW, UB = W + 1, 8  # dense waves and the sparse wave
             for b0 in range(0, nbatch + NW * UB, 1):             # every batch slot a round can touch, surplus ones included
                 p = np.minimum(P0 + b0 * WAVE + lanes, P1 - 1)
                 assert (p >= P0).all()
@@ -126,8 +126,7 @@ def test_every_load_stays_inside_its_array(M, N, bits, B):
     size = {"x": 2 * N * B, "qidx": M * N * bits // 8, "lut": M * 2 * (1 << bits), "rowptr": 4 * (M + 1), "cols": 4 * nnz, "vals": 2 * nnz}
     if B == 1:
         # rows per workgroup as the launcher picks them
-        waves = (N + SLICE - 1) // SLICE + 1
-        R = 4 if ((M + 3) // 4) * waves <= 256 * 4 * 8 else 8
+        R = 8 if (N + SLICE - 1) // SLICE >= 8 else 4
         reads = list(one_column_kernel_reads(M, N, bits, rowptr, R)) + list(one_column_kernel_reads(M, N, bits, rowptr, 12 - R))
     else:
         reads = list(sixteen_column_kernel_reads(M, N, bits, B, rowptr))
