@@ -97,8 +97,27 @@ int sqllm_csr_spmv(int M, int N, long long nnz, int B,
  * entry points.                                                                                          */
 int sqllm_dense_sparse_matvec(int M, int N, int bits, long long nnz, int B,
                               const void* qidx, const void* lut,
-                              const int* rowptr, const int* cols, const void* vals,
+                              const int* rowptr, const int* cols, const void* vals, const void* plan,
                               const void* x, void* y, void* stream);
+
+/* Plan of the sparse term: a one-time re-layout of the CSR arrays of a (static) weight matrix for the one-column kernel
+ * (Sec. 4.3 / App. C balance the nonzeros over the threads at run time; weights do not change, so the balancing can be done
+ * once).  The nonzeros of every workgroup's rows are stored as groups of 16 entries of one row -- column and fp16 value
+ * packed into one 32-bit word -- at a position the kernel derives from its workgroup index, with an overflow list for heavy
+ * rows.  With a plan the matvec requests its nonzeros at wave start (no row-pointer hop), reads 4 instead of 6 bytes per
+ * nonzero (plus the padding of the groups) and sums a row's group with a fixed 16-lane reduction, cheap enough for the dense
+ * waves to carry the sparse term.  It pays where the rows' nonzero counts are moderate (a workgroup whose rows hold far more
+ * than the average goes through the overflow list, a second dependent fetch); a caller may build it per layer or not at all.
+ *   sqllm_csr_plan_bytes   size of the plan buffer for (M, N, nnz), a multiple of 256; host pointer `bytes_out`.
+ *   sqllm_csr_plan_build   fills `plan` (device, 256-byte aligned, at least that many bytes) from rowptr / cols / vals on
+ *                          `stream`; N must not exceed 32768 columns (15-bit column field; SQLLM_MAX_N is below that).
+ * `plan` arguments: NULL, or a plan built for exactly this (M, N, nnz) and these CSR arrays.  It is used by calls with B == 1
+ * that have a dense term and nnz > 0 (sqllm_dense_sparse_matvec, sqllm_dense_sparse_matvec_multi); rowptr / cols / vals are
+ * then not read and may be NULL.  Calls with B >= 2 ignore the plan and need the CSR arrays.  The result is within the same
+ * tolerance of the definition with and without a plan; the order of the fp32 additions differs, so the last bit of y may. */
+int sqllm_csr_plan_bytes(int M, int N, long long nnz, size_t* bytes_out);
+int sqllm_csr_plan_build(int M, int N, long long nnz, const int* rowptr, const int* cols, const void* vals,
+                         void* plan, size_t bytes, void* stream);
 
 /* Several independent layers, one activation vector each (the per-token stack of matvecs of Sec. 4.3, last paragraph: q, k, v of
  * a decoder block share an input and do not depend on each other, gate and up likewise), in as few kernel launches as possible.
@@ -120,6 +139,7 @@ typedef struct {
     const int* rowptr;
     const int* cols;
     const void* vals;
+    const void* plan; /* NULL or the layer's plan (see sqllm_csr_plan_build); a launch also ends where this changes */
     const void* x;
     void* y;
 } sqllm_layer;

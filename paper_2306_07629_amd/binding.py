@@ -15,6 +15,7 @@ STATUS_NAMES = ["SQLLM_OK", "SQLLM_ERR_NULL", "SQLLM_ERR_BITS", "SQLLM_ERR_SHAPE
                 "SQLLM_ERR_BATCH", "SQLLM_ERR_HIP", "SQLLM_ERR_DEVICE"]
 
 EXPORTS = ["sqllm_lut_gemv", "sqllm_csr_spmv", "sqllm_dense_sparse_matvec", "sqllm_dense_sparse_matvec_multi", "sqllm_csr_spmv_rowwise",
+           "sqllm_csr_plan_bytes", "sqllm_csr_plan_build",
            "sqllm_unpack_indices", "sqllm_dequantize", "sqllm_fp16_gemv", "sqllm_algorithmic_bytes",
            "sqllm_quantize_workspace_bytes", "sqllm_quantize_layer", "sqllm_quantize_layer_noalloc", "sqllm_extraction_counts",
            "sqllm_last_error_string", "sqllm_status_string", "sqllm_version"]
@@ -24,7 +25,7 @@ class LayerDesc(ctypes.Structure):
     """sqllm_layer of include/sqllm.h"""
     _fields_ = [("M", ctypes.c_int), ("N", ctypes.c_int), ("bits", ctypes.c_int), ("nnz", ctypes.c_longlong),
                 ("qidx", ctypes.c_void_p), ("lut", ctypes.c_void_p), ("rowptr", ctypes.c_void_p), ("cols", ctypes.c_void_p),
-                ("vals", ctypes.c_void_p), ("x", ctypes.c_void_p), ("y", ctypes.c_void_p)]
+                ("vals", ctypes.c_void_p), ("plan", ctypes.c_void_p), ("x", ctypes.c_void_p), ("y", ctypes.c_void_p)]
 
 
 class SqllmError(RuntimeError):
@@ -45,7 +46,9 @@ def lib() -> ctypes.CDLL:
         L.sqllm_lut_gemv.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
         L.sqllm_csr_spmv.argtypes = [i32, i32, i64, i32, vp, vp, vp, vp, vp, i32, vp]
         L.sqllm_csr_spmv_rowwise.argtypes = [i32, i32, i64, i32, vp, vp, vp, vp, vp, i32, vp]
-        L.sqllm_dense_sparse_matvec.argtypes = [i32, i32, i32, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.sqllm_dense_sparse_matvec.argtypes = [i32, i32, i32, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.sqllm_csr_plan_bytes.argtypes = [i32, i32, i64, ctypes.POINTER(ctypes.c_size_t)]
+        L.sqllm_csr_plan_build.argtypes = [i32, i32, i64, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.sqllm_dense_sparse_matvec_multi.argtypes = [i32, ctypes.POINTER(LayerDesc), vp]
         L.sqllm_unpack_indices.argtypes = [i32, i32, i32, vp, vp, vp]
         L.sqllm_dequantize.argtypes = [i32, i32, i32, vp, vp, vp, vp]
@@ -99,9 +102,19 @@ def sqllm_csr_spmv_rowwise(M, N, nnz, B, rowptr, cols, vals, x, y, accumulate=0,
     _check(lib().sqllm_csr_spmv_rowwise(M, N, nnz, B, _ptr(rowptr), _ptr(cols), _ptr(vals), _ptr(x), _ptr(y), int(accumulate), _stream(stream)))
 
 
-def sqllm_dense_sparse_matvec(M, N, bits, nnz, B, qidx, lut, rowptr, cols, vals, x, y, stream=None):
-    _check(lib().sqllm_dense_sparse_matvec(M, N, bits, nnz, B, _ptr(qidx), _ptr(lut), _ptr(rowptr), _ptr(cols), _ptr(vals),
+def sqllm_dense_sparse_matvec(M, N, bits, nnz, B, qidx, lut, rowptr, cols, vals, x, y, stream=None, plan=None):
+    _check(lib().sqllm_dense_sparse_matvec(M, N, bits, nnz, B, _ptr(qidx), _ptr(lut), _ptr(rowptr), _ptr(cols), _ptr(vals), _ptr(plan),
                                            _ptr(x), _ptr(y), _stream(stream)))
+
+
+def sqllm_csr_plan_bytes(M, N, nnz) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().sqllm_csr_plan_bytes(int(M), int(N), int(nnz), ctypes.byref(n)))
+    return int(n.value)
+
+
+def sqllm_csr_plan_build(M, N, nnz, rowptr, cols, vals, plan, nbytes, stream=None):
+    _check(lib().sqllm_csr_plan_build(int(M), int(N), int(nnz), _ptr(rowptr), _ptr(cols), _ptr(vals), _ptr(plan), int(nbytes), _stream(stream)))
 
 
 def _addr(t):
@@ -111,11 +124,14 @@ def _addr(t):
 
 
 def layer_descriptors(layers):
-    """ctypes array of sqllm_layer from (M, N, bits, nnz, qidx, lut, rowptr, cols, vals, x, y) tuples (tensors or raw addresses)"""
+    """ctypes array of sqllm_layer from (M, N, bits, nnz, qidx, lut, rowptr, cols, vals, x, y[, plan]) tuples (tensors or raw
+    addresses)"""
     arr = (LayerDesc * len(layers))()
-    for d, (M, N, bits, nnz, qidx, lut, rowptr, cols, vals, x, y) in zip(arr, layers):
+    for d, t in zip(arr, layers):
+        M, N, bits, nnz, qidx, lut, rowptr, cols, vals, x, y = t[:11]
         d.M, d.N, d.bits, d.nnz = M, N, bits, nnz
-        d.qidx, d.lut, d.rowptr, d.cols, d.vals, d.x, d.y = (_addr(t) for t in (qidx, lut, rowptr, cols, vals, x, y))
+        d.qidx, d.lut, d.rowptr, d.cols, d.vals, d.x, d.y = (_addr(v) for v in (qidx, lut, rowptr, cols, vals, x, y))
+        d.plan = _addr(t[11]) if len(t) > 11 else None
     return arr
 
 

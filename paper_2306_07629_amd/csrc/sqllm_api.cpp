@@ -63,6 +63,12 @@ int check_sparse(long long nnz, const int* rowptr, const int* cols, const void* 
     return SQLLM_OK;
 }
 
+int check_plan(long long nnz, const void* plan) {
+    if (nnz < 0 || nnz > 0x7FFFFFFFll) return fail(SQLLM_ERR_NNZ, "nnz = %lld outside 0..2^31-1", nnz);
+    if (misaligned(plan, 256)) return fail(SQLLM_ERR_ALIGN, "plan must be 256-byte aligned");
+    return SQLLM_OK;
+}
+
 int hip_fail(hipError_t e, const char* what) {
     return fail(SQLLM_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
@@ -90,7 +96,7 @@ int check_device() {
 }
 
 int run_matvec(int M, int N, int bits, long long nnz, int B, const void* qidx, const void* lut, const int* rowptr,
-               const int* cols, const void* vals, const void* x, void* y, int accumulate, void* stream) {
+               const int* cols, const void* vals, const void* plan, const void* x, void* y, int accumulate, void* stream) {
     if (M == 0) return SQLLM_OK;
     int st;
     if ((st = check_device())) return st;
@@ -98,7 +104,7 @@ int run_matvec(int M, int N, int bits, long long nnz, int B, const void* qidx, c
     memset(&g, 0, sizeof g);
     g.M = M; g.N = N; g.bits = bits; g.B = B; g.bt0 = 0; g.bn = B;
     g.accumulate = accumulate; g.nnz = nnz;
-    g.qidx = qidx; g.lut = lut; g.rowptr = rowptr; g.cols = cols; g.vals = vals; g.x = x; g.y = y;
+    g.qidx = qidx; g.lut = lut; g.rowptr = rowptr; g.cols = cols; g.vals = vals; g.x = x; g.y = y; g.plan = plan;
     const hipError_t e = sqllm::launch_matvec(g, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "matvec launch");
     return SQLLM_OK;
@@ -112,22 +118,48 @@ int sqllm_lut_gemv(int M, int N, int bits, int B, const void* qidx, const void* 
                    int accumulate, void* stream) {
     int st;
     if ((st = check_bits(bits)) || (st = check_shape(M, N, B)) || (st = check_dense_ptrs(qidx, lut)) || (st = check_xy(x, y))) return st;
-    return run_matvec(M, N, bits, 0, B, qidx, lut, nullptr, nullptr, nullptr, x, y, accumulate, stream);
+    return run_matvec(M, N, bits, 0, B, qidx, lut, nullptr, nullptr, nullptr, nullptr, x, y, accumulate, stream);
 }
 
 int sqllm_csr_spmv(int M, int N, long long nnz, int B, const int* rowptr, const int* cols, const void* vals,
                    const void* x, void* y, int accumulate, void* stream) {
     int st;
     if ((st = check_shape(M, N, B)) || (st = check_sparse(nnz, rowptr, cols, vals)) || (st = check_xy(x, y))) return st;
-    return run_matvec(M, N, 3, nnz, B, nullptr, nullptr, rowptr, cols, vals, x, y, accumulate, stream);
+    return run_matvec(M, N, 3, nnz, B, nullptr, nullptr, rowptr, cols, vals, nullptr, x, y, accumulate, stream);
 }
 
 int sqllm_dense_sparse_matvec(int M, int N, int bits, long long nnz, int B, const void* qidx, const void* lut,
-                              const int* rowptr, const int* cols, const void* vals, const void* x, void* y, void* stream) {
+                              const int* rowptr, const int* cols, const void* vals, const void* plan, const void* x, void* y, void* stream) {
     int st;
+    const bool planned = plan != nullptr && B == 1 && nnz > 0;       // the CSR arrays are then not read
     if ((st = check_bits(bits)) || (st = check_shape(M, N, B)) || (st = check_dense_ptrs(qidx, lut)) ||
-        (st = check_sparse(nnz, rowptr, cols, vals)) || (st = check_xy(x, y))) return st;
-    return run_matvec(M, N, bits, nnz, B, qidx, lut, rowptr, cols, vals, x, y, 0, stream);
+        (st = planned ? check_plan(nnz, plan) : check_sparse(nnz, rowptr, cols, vals)) || (st = check_xy(x, y))) return st;
+    return run_matvec(M, N, bits, nnz, B, qidx, lut, rowptr, cols, vals, planned ? plan : nullptr, x, y, 0, stream);
+}
+
+int sqllm_csr_plan_bytes(int M, int N, long long nnz, size_t* bytes_out) {
+    int st;
+    if ((st = check_shape(M, N, 1))) return st;
+    if (nnz < 0 || nnz > 0x7FFFFFFFll) return fail(SQLLM_ERR_NNZ, "nnz = %lld outside 0..2^31-1", nnz);
+    if (!bytes_out) return fail(SQLLM_ERR_NULL, "bytes_out must not be NULL");
+    *bytes_out = sqllm::plan_layout(M, N, nnz).bytes;
+    return SQLLM_OK;
+}
+
+int sqllm_csr_plan_build(int M, int N, long long nnz, const int* rowptr, const int* cols, const void* vals,
+                         void* plan, size_t bytes, void* stream) {
+    int st;
+    if ((st = check_shape(M, N, 1)) || (st = check_sparse(nnz, rowptr, cols, vals))) return st;
+    if (!plan) return fail(SQLLM_ERR_NULL, "plan must not be NULL");
+    if (!rowptr) return fail(SQLLM_ERR_NULL, "rowptr must not be NULL");
+    if (misaligned(plan, 256)) return fail(SQLLM_ERR_ALIGN, "plan must be 256-byte aligned");
+    const size_t need = sqllm::plan_layout(M, N, nnz).bytes;
+    if (bytes < need) return fail(SQLLM_ERR_SHAPE, "plan buffer of %zu bytes, %zu needed", bytes, need);
+    if (M == 0) return SQLLM_OK;
+    if ((st = check_device())) return st;
+    const hipError_t e = sqllm::launch_plan_build(M, N, nnz, rowptr, cols, vals, plan, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "plan build launch");
+    return SQLLM_OK;
 }
 
 int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* stream) {
@@ -138,8 +170,9 @@ int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* 
     int st;
     for (int l = 0; l < count; ++l) {
         const sqllm_layer& L = layers[l];
+        const bool planned = L.plan != nullptr && L.nnz > 0;
         if ((st = check_bits(L.bits)) || (st = check_shape(L.M, L.N, 1)) || (st = check_dense_ptrs(L.qidx, L.lut)) ||
-            (st = check_sparse(L.nnz, L.rowptr, L.cols, L.vals)) || (st = check_xy(L.x, L.y))) {
+            (st = planned ? check_plan(L.nnz, L.plan) : check_sparse(L.nnz, L.rowptr, L.cols, L.vals)) || (st = check_xy(L.x, L.y))) {
             char msg[200];
             snprintf(msg, sizeof msg, "%s", g_err);
             return fail(st, "layer %d: %s", l, msg);
@@ -154,13 +187,15 @@ int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* 
     while (l < count) {
         sqllm::MultiArgs m;
         memset(&m, 0, sizeof m);
-        const int cls = sqllm::multi_rows_per_workgroup(layers[l].N);
-        while (l < count && m.count < sqllm::kMaxLayersPerLaunch && sqllm::multi_rows_per_workgroup(layers[l].N) == cls) {
+        // a launch holds layers of one class: rows per workgroup, and sparse term from a plan or from the CSR arrays
+        auto cls_of = [](const sqllm_layer& L) { return sqllm::multi_rows_per_workgroup(L.N) * 2 + ((L.plan != nullptr && L.nnz > 0) ? 1 : 0); };
+        const int cls = cls_of(layers[l]);
+        while (l < count && m.count < sqllm::kMaxLayersPerLaunch && cls_of(layers[l]) == cls) {
             const sqllm_layer& L = layers[l];
             if (L.M > 0) {
                 const int k = m.count++;
                 m.M[k] = L.M; m.N[k] = L.N; m.nnz[k] = L.nnz; m.qidx[k] = L.qidx; m.lut[k] = L.lut; m.rowptr[k] = L.rowptr; m.cols[k] = L.cols;
-                m.vals[k] = L.vals; m.x[k] = L.x; m.y[k] = L.y;
+                m.vals[k] = L.vals; m.x[k] = L.x; m.y[k] = L.y; m.plan[k] = (L.plan != nullptr && L.nnz > 0) ? L.plan : nullptr;
             }
             ++l;
         }

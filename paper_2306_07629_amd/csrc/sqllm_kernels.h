@@ -16,7 +16,25 @@ struct MatvecArgs {
     const void* vals;
     const void* x;
     void* y;
+    const void* plan;       // nullptr, or the plan of the sparse term (one-column kernel only): rowptr / cols / vals are then not read
+    int plan_c;             // slot batches per workgroup of that plan (set by the launcher)
 };
+
+// ---- Plan of the sparse term (built once per matrix, caller-owned device buffer).  The nonzeros of every workgroup's rows are
+// re-laid-out as GROUPS of 16 entries of one row (zero-padded), four groups to a BATCH of 64 lanes:
+//   entry  u32 = column (15 bits) | fp16 value << 16          tag byte of a group = valid << 7 | (count - 1) << 3 | row within the workgroup
+// The first `C` batches of workgroup b sit in a fixed slot (batch b C + k), so the kernel can request them at wave start from its
+// workgroup index alone; what does not fit (a heavy row) goes to an overflow region described by one (first batch, batches) pair
+// per workgroup.  Every offset below follows from (M, N, nnz) alone, so the host never has to read the plan.
+struct PlanLayout {
+    int R;                      // rows per workgroup of the one-column kernel for this row width (4 or 8)
+    int n_wg;                   // workgroups = ceil(M / R)
+    int C;                      // slot batches per workgroup
+    long long ov_cap;           // capacity of the overflow region in batches
+    size_t off_slot_entries, off_slot_tags, off_ov_desc, off_ov_entries, off_ov_tags, bytes;
+};
+PlanLayout plan_layout(int M, int N, long long nnz);
+hipError_t launch_plan_build(int M, int N, long long nnz, const int* rowptr, const int* cols, const void* vals, void* plan, hipStream_t s);
 
 // Several independent one-column layers in one launch (passed by value as kernel arguments)
 constexpr int kMaxLayersPerLaunch = 8;
@@ -32,6 +50,8 @@ struct MultiArgs {
     const void* vals[kMaxLayersPerLaunch];
     const void* x[kMaxLayersPerLaunch];
     void* y[kMaxLayersPerLaunch];
+    const void* plan[kMaxLayersPerLaunch];
+    int plan_c[kMaxLayersPerLaunch];            // filled by the launcher
 };
 int multi_rows_per_workgroup(int N);             // rows per workgroup of the one-column kernel for rows of N columns (4 or 8)
 hipError_t launch_matvec_multi(MultiArgs& m, int bits, hipStream_t s);

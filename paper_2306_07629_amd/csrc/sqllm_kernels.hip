@@ -485,6 +485,310 @@ __device__ __forceinline__ void matvec_block(const MatvecArgs& g, int block, int
     }
 }
 
+// ---------------------------------------------------------------------------------------------- sparse term from a plan
+// A plan (sqllm_kernels.h: PlanLayout) holds the nonzeros of every workgroup's rows as groups of 16 entries of one row, four
+// groups to a batch of 64 lanes, the first C batches of a workgroup in a slot found from the workgroup index alone.  Against the
+// CSR arrays this removes the first hop of the dependent chain (row pointers -> columns / values -> gathers), halves the loads
+// per nonzero (column and value share a dword) and replaces the segmented scan by a fixed 16-lane reduction -- cheap enough for
+// the dense waves to carry the sparse term themselves, so a workgroup needs no extra wave.
+struct PlanView {
+    const u32* slot_entries;    // [n_wg][C][64]
+    const uint8_t* slot_tags;   // [n_wg][C][4]   one tag byte per group
+    const int* ov_desc;         // [n_wg][2]      first overflow batch, overflow batches
+    const u32* ov_entries;      // [ov batches][64]
+    const uint8_t* ov_tags;     // [ov batches][4]
+    int C;
+    int ov_cap;                 // batches the overflow sections hold
+};
+
+template <int R>
+__device__ __forceinline__ PlanView plan_view(const void* plan, int M, long long nnz, int C) {
+    // the offsets of plan_layout() on the host; C comes with the kernel arguments (its formula needs a 64-bit division)
+    const size_t n_wg = (size_t)((M + R - 1) / R);
+    const size_t ov_cap = (size_t)((nnz / 16 + M) / 4) + n_wg + 1;
+    auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    const char* b = static_cast<const char*>(plan);
+    PlanView v;
+    size_t o = 0;
+    v.slot_entries = reinterpret_cast<const u32*>(b + o); o += up(n_wg * C * 256);
+    v.slot_tags = reinterpret_cast<const uint8_t*>(b + o); o += up(n_wg * C * 4);
+    v.ov_desc = reinterpret_cast<const int*>(b + o);      o += up(n_wg * 8);
+    v.ov_entries = reinterpret_cast<const u32*>(b + o);   o += up(ov_cap * 256);
+    v.ov_tags = reinterpret_cast<const uint8_t*>(b + o);
+    v.C = C;
+    v.ov_cap = (int)ov_cap;
+    return v;
+}
+
+// sum over each 16-lane row, valid in its lane 15
+__device__ __forceinline__ float row16_sum_to_lane15(float v) {
+    v += dpp_f<kRowShr1>(0.f, v);
+    v += dpp_f<kRowShr2>(0.f, v);
+    v += dpp_f<kRowShr4>(0.f, v);
+    v += dpp_f<kRowShr8>(0.f, v);
+    return v;
+}
+
+// one batch: entry, gathered activation and the tag byte of the lane's group (valid << 7 | (count - 1) << 3 | row) per lane ->
+// the row sums go to the wave's slots
+__device__ __forceinline__ void plan_batch_reduce(u32 entry, u32 xv, u32 tb, int lane, float* __restrict__ slots) {
+    const bool ok = (tb & 0x80u) && (u32)(lane & 15) <= ((tb >> 3) & 15u);
+    float v = ok ? half_bits_to_float((uint16_t)(entry >> 16)) * half_bits_to_float((uint16_t)xv) : 0.f;
+    v = row16_sum_to_lane15(v);
+    // one add per group, in group order (instructions of a wave reach the LDS in order): a fixed order of additions per slot
+#pragma unroll
+    for (int gi = 0; gi < 4; ++gi)
+        if (lane == 16 * gi + 15 && (tb & 0x80u)) lds_add(slots + (tb & 7u), v);
+}
+
+template <int BITS, int R, int D>
+__device__ __forceinline__ void matvec_planned_block(const MatvecArgs& g, int block, int W) {
+    static_assert(D >= 2 && D <= R && (R == 4 || R == 8), "prefetch depth, rows per workgroup");
+    constexpr int K = 1 << BITS;
+    constexpr int kRawUnit = TableShape<BITS>::kRawUnit;
+    constexpr int UE = 1;                                            // slot batches per wave (C <= UE W)
+    constexpr int UP = 2;                                            // overflow batches per wave requested ahead
+    constexpr int TD = TableShape<BITS>::kTableDwords;
+    __shared__ __align__(8) u32 tables[R * TD];
+    __shared__ __align__(16) uint16_t raw[R * K];
+    __shared__ float part[kMaxDenseWaves * 4 * R];                   // dense:  [wave][16-lane row][r]
+    __shared__ float spart[kMaxDenseWaves * R];                      // sparse: [wave][r]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r0 = block * R;
+    const int nrows = min(R, g.M - r0);
+    const uint16_t* __restrict__ x = static_cast<const uint16_t*>(g.x);
+    const PlanView pv = plan_view<R>(g.plan, g.M, g.nnz, g.plan_c);
+    float* myslots = spart + wave * R;
+    if (lane < R) myslots[lane] = 0.f;
+
+    // ---- Issue order: (wave 0: fp16 tables), activations, first D rows of the index stream, this wave's slot batches
+    constexpr int LPR = TableShape<BITS>::kRowBytes / kRawUnit;
+    const int my_rows = wave == 0 ? R : 0;
+    const int bu = lane / LPR;
+    u32x4 rawv = {0, 0, 0, 0};
+    if (lane < my_rows * LPR) {
+        const int row = min(r0 + bu, g.M - 1);
+        const char* src = static_cast<const char*>(g.lut) + (size_t)row * TableShape<BITS>::kRowBytes + (lane % LPR) * kRawUnit;
+        if constexpr (kRawUnit == 16) {
+            rawv = *reinterpret_cast<const u32x4*>(src);
+        } else {
+            const u32x2 v = *reinterpret_cast<const u32x2*>(src);
+            rawv.x = v.x; rawv.y = v.y;
+        }
+    }
+    const int j0 = wave * kSliceCols + lane * kLaneElems;
+    const bool live = j0 < g.N;
+    const int j0c = live ? j0 : g.N - kLaneElems;
+    u32 xr[16];
+    load_x(x, j0c, xr);
+    const size_t row_dwords = (size_t)g.N * BITS / 32;
+    const u32* __restrict__ qlane = static_cast<const u32*>(g.qidx) + (size_t)(j0c / 32) * BITS;
+    LaneChunk<BITS> c[R];
+#pragma unroll
+    for (int u = 0; u < D; ++u) c[u] = load_chunk<BITS>(qlane + (size_t)min(r0 + u, g.M - 1) * row_dwords);
+    // Slot batch k of this wave is batch wave + k W of the workgroup's slot; past the slot (>= C) the last batch is re-read and its
+    // tags are cleared.  Entries, tag bytes (one per group, fetched by the group's own lanes) and the overflow descriptor all come
+    // through vector loads: a scalar load would have to be waited for together with every LDS operation of the wave.
+    u32 ent[UE], tags[UE], sx[UE], oe[UP], ot[UP];
+    int ov_first = 0, ov_nb = 0;
+#pragma unroll
+    for (int k = 0; k < UE; ++k) {
+        const int kb = min(wave + k * W, pv.C - 1);
+        const size_t sb = (size_t)block * pv.C + kb;
+        ent[k] = pv.slot_entries[sb * 64 + lane];
+        tags[k] = pv.slot_tags[sb * 4 + (lane >> 4)];
+    }
+    const int ovd = pv.ov_desc[2 * block + (lane & 1)];              // lane 0: first overflow batch, lane 1: their number
+    if (!live) {
+#pragma unroll
+        for (int p = 0; p < 16; ++p) xr[p] = 0;
+    }
+    if (my_rows > 0) {                                                // uniform
+        if (lane < my_rows * LPR) {
+            if constexpr (kRawUnit == 16) *reinterpret_cast<u32x4*>(raw + bu * K + (lane % LPR) * 8) = rawv;
+            else *reinterpret_cast<u32x2*>(raw + bu * K) = u32x2{rawv.x, rawv.y};
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        build_tables<BITS, R>(tables, raw, lane);
+    }
+    __syncthreads();
+    float acc[R];
+    u32 w[2][16];
+    lookup_chunk<BITS>(c[0], tables, w[0]);
+    if constexpr (D < R) c[D] = load_chunk<BITS>(qlane + (size_t)min(r0 + D, g.M - 1) * row_dwords);
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+        if (u + 1 < R) {
+            lookup_chunk<BITS>(c[u + 1], tables + (u + 1) * TD, w[(u + 1) & 1]);
+            if (u + 1 + D < R) c[(u + 1 + D) % R] = load_chunk<BITS>(qlane + (size_t)min(r0 + u + 1 + D, g.M - 1) * row_dwords);
+        }
+        // The activations of the slot batches are gathered once the last row of the index stream has been requested: memory
+        // results return in request order, so gathers issued earlier would stand between the wave and its next rows, and a
+        // gather has to wait for its entry first (the scheduling barrier keeps the compiler from moving that wait, and with it
+        // the request for the last row, the other way round).
+        // With them go the requests for this wave's first overflow batches (a workgroup with a heavy row has some): their
+        // place is known once the descriptor has arrived, which it has when the entries have.
+        if (u + 1 + D == R - 1 || (D == R - 1 && u == 0)) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < UE; ++k) sx[k] = x[ent[k] & 0x7FFFu];
+            ov_first = __builtin_amdgcn_readlane(ovd, 0);
+            ov_nb = __builtin_amdgcn_readlane(ovd, 1);
+#pragma unroll
+            for (int k = 0; k < UP; ++k) {
+                const int b = min(ov_first + min(wave + k * W, max(ov_nb - 1, 0)), pv.ov_cap - 1);
+                oe[k] = pv.ov_entries[(size_t)b * 64 + lane];
+                ot[k] = pv.ov_tags[(size_t)b * 4 + (lane >> 4)];
+            }
+        }
+        acc[u] = dot_chunk(w[u & 1], xr);
+        if (u + 1 < R) {
+#pragma unroll
+            for (int p = 0; p < 16; ++p) {
+                __builtin_amdgcn_sched_group_barrier(0x2, 2, 0);              // VALU: the offsets of one look-up
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);            // DS read
+                __builtin_amdgcn_sched_group_barrier(0x2, 1, 0);              // VALU: the products of one look-up
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    row_block_reduce<R>(acc, lane);
+    if (row_block_valid(lane) && (R == 8 || !(lane & 8))) part[(wave * 4 + (lane >> 4)) * R + row_block_class<R>(lane)] = acc[0];
+    // ---- sparse term: this wave's slot batches, then its share of the overflow batches
+#pragma unroll
+    for (int k = 0; k < UE; ++k)
+        if (wave + k * W < pv.C) plan_batch_reduce(ent[k], sx[k], tags[k], lane, myslots);    // uniform
+    if (wave < ov_nb) {                                                                       // uniform
+        u32 ox[UP];
+#pragma unroll
+        for (int k = 0; k < UP; ++k) ox[k] = x[oe[k] & 0x7FFFu];
+#pragma unroll
+        for (int k = 0; k < UP; ++k)
+            if (wave + k * W < ov_nb) plan_batch_reduce(oe[k], ox[k], ot[k], lane, myslots);
+    }
+    // what a very heavy row leaves after that: UO batches per wave and round, all requested before the first is used (the
+    // workgroup that owns such a row ends last, and every round costs it two memory latencies)
+    constexpr int UO = 8;
+    for (int ob = wave + UP * W; ob < ov_nb; ob += UO * W) {                                  // uniform
+        u32 e2[UO], t2[UO], x2[UO];
+#pragma unroll
+        for (int k = 0; k < UO; ++k) {
+            const int b = min(ob + k * W, ov_nb - 1);
+            e2[k] = pv.ov_entries[(size_t)(ov_first + b) * 64 + lane];
+            t2[k] = pv.ov_tags[(size_t)(ov_first + b) * 4 + (lane >> 4)];
+        }
+#pragma unroll
+        for (int k = 0; k < UO; ++k) x2[k] = x[e2[k] & 0x7FFFu];
+#pragma unroll
+        for (int k = 0; k < UO; ++k)
+            if (ob + k * W < ov_nb) plan_batch_reduce(e2[k], x2[k], t2[k], lane, myslots);
+    }
+    __syncthreads();
+    uint16_t* __restrict__ y = static_cast<uint16_t*>(g.y);
+    if (tid < nrows) {
+        float s = 0.f;
+        for (int w2 = 0; w2 < 4 * W; ++w2) s += part[w2 * R + tid];
+        for (int w2 = 0; w2 < W; ++w2) s += spart[w2 * R + tid];
+        y[r0 + tid] = float_to_half_bits(s);
+    }
+}
+
+template <int BITS, int R, int D>
+__global__ void __launch_bounds__(1024) matvec_planned_kernel(MatvecArgs g) {
+    matvec_planned_block<BITS, R, D>(g, blockIdx.x, blockDim.x >> 6);
+}
+
+template <int BITS, int R, int D>
+__global__ void __launch_bounds__(1024) matvec_planned_multi_kernel(MultiArgs m) {
+    int l = 0;
+#pragma unroll
+    for (int k = 1; k < kMaxLayersPerLaunch; ++k) l += (k < m.count && (int)blockIdx.x >= m.first_block[k]) ? 1 : 0;   // uniform
+    MatvecArgs g;
+    g.M = m.M[l]; g.N = m.N[l]; g.bits = BITS; g.B = 1; g.bt0 = 0; g.bn = 1; g.accumulate = 0; g.nnz = m.nnz[l];
+    g.qidx = m.qidx[l]; g.lut = m.lut[l]; g.rowptr = nullptr; g.cols = nullptr; g.vals = nullptr; g.x = m.x[l]; g.y = m.y[l]; g.plan = m.plan[l]; g.plan_c = m.plan_c[l];
+    const int W = (g.N + kSliceCols - 1) / kSliceCols;
+    if ((int)(threadIdx.x >> 6) >= W) return;
+    matvec_planned_block<BITS, R, D>(g, (int)blockIdx.x - m.first_block[l], W);
+}
+
+// ---- building a plan from the CSR arrays: count the batches of every workgroup, scan the overflow, fill
+__device__ __forceinline__ int plan_groups_of(int cnt) { return (cnt + 15) >> 4; }
+
+template <int R>
+__global__ void __launch_bounds__(256) plan_count_kernel(int M, int n_wg, int C, const int* __restrict__ rowptr, int* __restrict__ ov_desc) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= n_wg) return;
+    int groups = 0;
+    for (int i = 0; i < R; ++i) {
+        const int r = b * R + i;
+        if (r < M) groups += plan_groups_of(rowptr[r + 1] - rowptr[r]);
+    }
+    const int nb = (groups + 3) >> 2;
+    ov_desc[2 * b + 1] = nb > C ? nb - C : 0;
+}
+
+// exclusive scan of the overflow counts over the workgroups (one block; n_wg is a few thousand)
+__global__ void __launch_bounds__(1024) plan_scan_kernel(int n_wg, int* __restrict__ ov_desc) {
+    __shared__ int sums[1024];
+    const int t = threadIdx.x;
+    const int per = (n_wg + 1023) / 1024;
+    const int lo = min(t * per, n_wg), hi = min(lo + per, n_wg);
+    int s = 0;
+    for (int b = lo; b < hi; ++b) s += ov_desc[2 * b + 1];
+    sums[t] = s;
+    __syncthreads();
+    for (int d = 1; d < 1024; d <<= 1) {
+        const int v = t >= d ? sums[t - d] : 0;
+        __syncthreads();
+        sums[t] += v;
+        __syncthreads();
+    }
+    int run = sums[t] - s;
+    for (int b = lo; b < hi; ++b) { ov_desc[2 * b] = run; run += ov_desc[2 * b + 1]; }
+}
+
+// one wave per workgroup of the matvec: lane l fills entry l of every batch
+template <int R>
+__global__ void __launch_bounds__(64) plan_fill_kernel(int M, int C, const int* __restrict__ rowptr, const int* __restrict__ cols, const uint16_t* __restrict__ vals,
+                                                       u32* __restrict__ slot_entries, uint8_t* __restrict__ slot_tags, const int* __restrict__ ov_desc,
+                                                       u32* __restrict__ ov_entries, uint8_t* __restrict__ ov_tags) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    int gp[R + 1], rs[R + 1];                                        // first group / first nonzero of every row of the workgroup (uniform)
+    gp[0] = 0;
+#pragma unroll
+    for (int i = 0; i <= R; ++i) rs[i] = rowptr[min(b * R + i, M)];
+#pragma unroll
+    for (int i = 0; i < R; ++i) gp[i + 1] = gp[i] + plan_groups_of(rs[i + 1] - rs[i]);
+    const int groups = gp[R], nb = (groups + 3) >> 2;
+    const int ov_first = ov_desc[2 * b];
+    const int total = max(nb, C);                                    // unused slot batches are cleared
+    for (int k = 0; k < total; ++k) {
+        const int gidx = 4 * k + (lane >> 4);
+        u32 entry = 0, tag = 0;
+        if (gidx < groups) {
+            int i = 0;
+#pragma unroll
+            for (int t = 1; t < R; ++t) i += gidx >= gp[t] ? 1 : 0;
+            const int j = gidx - gp[i];
+            const int left = rs[i + 1] - rs[i] - 16 * j;              // >= 1
+            const int cnt = left < 16 ? left : 16;
+            const int p = rs[i] + 16 * j + (lane & 15);
+            if ((lane & 15) < cnt) entry = ((u32)cols[p] & 0x7FFFu) | ((u32)vals[p] << 16);
+            tag = 0x80u | ((u32)(cnt - 1) << 3) | (u32)i;
+        }
+        if (k < C) {
+            slot_entries[((size_t)b * C + k) * 64 + lane] = entry;
+            if ((lane & 15) == 0) slot_tags[((size_t)b * C + k) * 4 + (lane >> 4)] = (uint8_t)tag;
+        } else {
+            ov_entries[((size_t)ov_first + k - C) * 64 + lane] = entry;
+            if ((lane & 15) == 0) ov_tags[((size_t)ov_first + k - C) * 4 + (lane >> 4)] = (uint8_t)tag;
+        }
+    }
+}
+
 template <int BITS, int R, int D>
 __global__ void __launch_bounds__(1024) matvec_kernel(MatvecArgs g) {
     matvec_block<BITS, R, D>(g, blockIdx.x, blockDim.x >> 6);
@@ -503,7 +807,7 @@ __global__ void __launch_bounds__(1024) matvec_multi_kernel(MultiArgs m) {
     for (int k = 1; k < kMaxLayersPerLaunch; ++k) l += (k < m.count && (int)blockIdx.x >= m.first_block[k]) ? 1 : 0;   // uniform
     MatvecArgs g;
     g.M = m.M[l]; g.N = m.N[l]; g.bits = BITS; g.B = 1; g.bt0 = 0; g.bn = 1; g.accumulate = 0; g.nnz = m.nnz[l];
-    g.qidx = m.qidx[l]; g.lut = m.lut[l]; g.rowptr = m.rowptr[l]; g.cols = m.cols[l]; g.vals = m.vals[l]; g.x = m.x[l]; g.y = m.y[l];
+    g.qidx = m.qidx[l]; g.lut = m.lut[l]; g.rowptr = m.rowptr[l]; g.cols = m.cols[l]; g.vals = m.vals[l]; g.x = m.x[l]; g.y = m.y[l]; g.plan = nullptr;
     const int NW = (g.N + kSliceCols - 1) / kSliceCols + (g.nnz > 0 ? 1 : 0);
     if ((int)(threadIdx.x >> 6) >= NW) return;
     matvec_block<BITS, R, D>(g, (int)blockIdx.x - m.first_block[l], NW);
@@ -1088,6 +1392,55 @@ static hipError_t launch_matvec_one(const MatvecArgs& g, hipStream_t s) {
     return g.qidx && multi_rows_per_workgroup(g.N) == 8 ? launch_matvec_r<BITS, 8, 2>(g, s) : launch_matvec_r<BITS, 4, 2>(g, s);
 }
 
+PlanLayout plan_layout(int M, int N, long long nnz) {
+    PlanLayout L;
+    L.R = multi_rows_per_workgroup(N);
+    L.n_wg = (M + L.R - 1) / L.R;
+    const long long n_wg = L.n_wg;
+    const long long groups = nnz / 16 + M / 2 + 1;                  // a row of c nonzeros has ceil(c / 16) groups
+    const int W = (N + kSliceCols - 1) / kSliceCols;
+    long long C = n_wg > 0 ? (groups * 115 / 100 + 4 * n_wg - 1) / (4 * n_wg) : 1;   // 15 % above the mean; a wave carries at most two slot batches
+    L.C = (int)(C < 1 ? 1 : (C > W ? W : C));
+    L.ov_cap = (nnz / 16 + M) / 4 + n_wg + 1;
+    auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    size_t o = 0;
+    L.off_slot_entries = o; o += up((size_t)n_wg * L.C * 256);
+    L.off_slot_tags = o;    o += up((size_t)n_wg * L.C * 4);
+    L.off_ov_desc = o;      o += up((size_t)n_wg * 8);
+    L.off_ov_entries = o;   o += up((size_t)L.ov_cap * 256);
+    L.off_ov_tags = o;      o += up((size_t)L.ov_cap * 4);
+    L.bytes = o;
+    return L;
+}
+
+hipError_t launch_plan_build(int M, int N, long long nnz, const int* rowptr, const int* cols, const void* vals, void* plan, hipStream_t s) {
+    const PlanLayout L = plan_layout(M, N, nnz);
+    if (L.n_wg == 0) return hipSuccess;
+    char* b = static_cast<char*>(plan);
+    u32* slot_entries = reinterpret_cast<u32*>(b + L.off_slot_entries);
+    uint8_t* slot_tags = reinterpret_cast<uint8_t*>(b + L.off_slot_tags);
+    int* ov_desc = reinterpret_cast<int*>(b + L.off_ov_desc);
+    u32* ov_entries = reinterpret_cast<u32*>(b + L.off_ov_entries);
+    uint8_t* ov_tags = reinterpret_cast<uint8_t*>(b + L.off_ov_tags);
+    const uint16_t* v16 = static_cast<const uint16_t*>(vals);
+    if (L.R == 8) hipLaunchKernelGGL((plan_count_kernel<8>), dim3((L.n_wg + 255) / 256), dim3(256), 0, s, M, L.n_wg, L.C, rowptr, ov_desc);
+    else hipLaunchKernelGGL((plan_count_kernel<4>), dim3((L.n_wg + 255) / 256), dim3(256), 0, s, M, L.n_wg, L.C, rowptr, ov_desc);
+    hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, s, L.n_wg, ov_desc);
+    if (L.R == 8) hipLaunchKernelGGL((plan_fill_kernel<8>), dim3(L.n_wg), dim3(64), 0, s, M, L.C, rowptr, cols, v16, slot_entries, slot_tags, ov_desc, ov_entries, ov_tags);
+    else hipLaunchKernelGGL((plan_fill_kernel<4>), dim3(L.n_wg), dim3(64), 0, s, M, L.C, rowptr, cols, v16, slot_entries, slot_tags, ov_desc, ov_entries, ov_tags);
+    return hipGetLastError();
+}
+
+template <int BITS>
+static hipError_t launch_matvec_planned(const MatvecArgs& g0, hipStream_t s) {
+    MatvecArgs g = g0;
+    g.plan_c = plan_layout(g.M, g.N, g.nnz).C;
+    const int W = (g.N + kSliceCols - 1) / kSliceCols;
+    if (multi_rows_per_workgroup(g.N) == 8) hipLaunchKernelGGL((matvec_planned_kernel<BITS, 8, 2>), dim3((g.M + 7) / 8), dim3(W * kWave), 0, s, g);
+    else hipLaunchKernelGGL((matvec_planned_kernel<BITS, 4, 2>), dim3((g.M + 3) / 4), dim3(W * kWave), 0, s, g);
+    return hipGetLastError();
+}
+
 template <int BITS, int R>
 static hipError_t launch_multi_r(MultiArgs& m, hipStream_t s) {
     int total = 0, waves = 1;
@@ -1098,7 +1451,16 @@ static hipError_t launch_multi_r(MultiArgs& m, hipStream_t s) {
     }
     for (int l = m.count; l <= kMaxLayersPerLaunch; ++l) m.first_block[l] = total;
     if (total == 0) return hipSuccess;
-    hipLaunchKernelGGL((matvec_multi_kernel<BITS, R, 2>), dim3(total), dim3(waves * kWave), 0, s, m);
+    if (m.plan[0]) {
+        int w2 = 1;
+        for (int l = 0; l < m.count; ++l) {
+            w2 = max(w2, (m.N[l] + kSliceCols - 1) / kSliceCols);
+            m.plan_c[l] = plan_layout(m.M[l], m.N[l], m.nnz[l]).C;
+        }
+        hipLaunchKernelGGL((matvec_planned_multi_kernel<BITS, R, 2>), dim3(total), dim3(w2 * kWave), 0, s, m);
+    } else {
+        hipLaunchKernelGGL((matvec_multi_kernel<BITS, R, 2>), dim3(total), dim3(waves * kWave), 0, s, m);
+    }
     return hipGetLastError();
 }
 
@@ -1149,6 +1511,8 @@ static hipError_t launch_matvec_b16(const MatvecArgs& g, hipStream_t s) {
 hipError_t launch_matvec(const MatvecArgs& g, hipStream_t s) {
     // one column: the vector-ALU kernel; two or more: one launch of the 16-column kernel (every weight is decoded once for all
     // columns), also without a dense term
+    if (g.B == 1 && g.plan && g.qidx && g.nnz > 0 && !g.accumulate)
+        return g.bits == 2 ? launch_matvec_planned<2>(g, s) : (g.bits == 3 ? launch_matvec_planned<3>(g, s) : launch_matvec_planned<4>(g, s));
     if (g.B == 1) return g.bits == 2 ? launch_matvec_one<2>(g, s) : (g.bits == 3 ? launch_matvec_one<3>(g, s) : launch_matvec_one<4>(g, s));
     return g.bits == 2 ? launch_matvec_b16<2>(g, s) : (g.bits == 3 ? launch_matvec_b16<3>(g, s) : launch_matvec_b16<4>(g, s));
 }

@@ -23,6 +23,15 @@ class DeviceLayer:
         self.vals = up(layer.vals, np.int16) if self.nnz else None
         self.x = up(layer.x, np.int16)
         self.y = torch.zeros((self.M, self.B), dtype=torch.int16, device=dev)
+        self.plan = None
+
+    def build_plan(self, stream=None):
+        """One-time re-layout of the CSR arrays for the one-column kernel (sqllm_csr_plan_build); matvec() then passes it on."""
+        if self.nnz and self.plan is None:
+            nbytes = _b.sqllm_csr_plan_bytes(self.M, self.N, self.nnz)
+            self.plan = self.torch.empty(nbytes, dtype=self.torch.uint8, device=self.qidx.device)
+            _b.sqllm_csr_plan_build(self.M, self.N, self.nnz, self.rowptr, self.cols, self.vals, self.plan, nbytes, stream)
+        return self
 
     def clone_weights(self):
         """A second copy of the weight arrays at different addresses (for cold-cache timing)."""
@@ -31,18 +40,19 @@ class DeviceLayer:
         other.qidx = self.qidx.clone(); other.lut = self.lut.clone(); other.rowptr = self.rowptr.clone()
         other.cols = None if self.cols is None else self.cols.clone()
         other.vals = None if self.vals is None else self.vals.clone()
+        other.plan = None if self.plan is None else self.plan.clone()
         other.y = self.y.clone()
         return other
 
     # --- library calls (each enqueues on the current stream)
     def matvec(self, stream=None):
         _b.sqllm_dense_sparse_matvec(self.M, self.N, self.bits, self.nnz, self.B, self.qidx, self.lut, self.rowptr,
-                                     self.cols, self.vals, self.x, self.y, stream)
+                                     self.cols, self.vals, self.x, self.y, stream, plan=self.plan)
         return self.y
 
     def descriptor(self):
         """the tuple binding.layer_descriptors() takes (one activation column)"""
-        return (self.M, self.N, self.bits, self.nnz, self.qidx, self.lut, self.rowptr, self.cols, self.vals, self.x, self.y)
+        return (self.M, self.N, self.bits, self.nnz, self.qidx, self.lut, self.rowptr, self.cols, self.vals, self.x, self.y, self.plan)
 
     def lut_gemv(self, accumulate=0, stream=None):
         _b.sqllm_lut_gemv(self.M, self.N, self.bits, self.B, self.qidx, self.lut, self.x, self.y, accumulate, stream)

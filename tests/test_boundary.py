@@ -101,6 +101,34 @@ def test_multi_layer_argument_errors():
     f([(0, 128, 3, 0, A, A, None, None, None, A, A)] * 3)          # only empty layers: nothing is enqueued, no HIP call
 
 
+def test_plan_argument_errors_and_sizes():
+    n = sq.sqllm_csr_plan_bytes(4096, 4096, 75497)
+    assert n % 256 == 0 and 75497 * 4 < n < 75497 * 24     # slots 15 % above the mean plus a worst-case overflow region
+    assert sq.sqllm_csr_plan_bytes(8, 128, 0) % 256 == 0 and sq.sqllm_csr_plan_bytes(0, 128, 0) >= 0
+    assert sq.sqllm_csr_plan_bytes(22016, 8192, 811598) > sq.sqllm_csr_plan_bytes(11008, 8192, 405799)
+    for bad in ((4, 100, 5), (-1, 128, 5), (4, 128, -1)):
+        with pytest.raises(sq.SqllmError):
+            sq.sqllm_csr_plan_bytes(*bad)
+    f = sq.sqllm_csr_plan_build
+    nb = sq.sqllm_csr_plan_bytes(4, 128, 5)
+    expect("SQLLM_ERR_NULL", f, 4, 128, 5, A, A, A, None, nb)
+    expect("SQLLM_ERR_NULL", f, 4, 128, 5, None, A, A, A, nb)
+    expect("SQLLM_ERR_ALIGN", f, 4, 128, 5, A, A, A, A + 128, nb)
+    expect("SQLLM_ERR_SHAPE", f, 4, 128, 5, A, A, A, A, nb - 256)
+    expect("SQLLM_ERR_SHAPE", f, 4, 130, 5, A, A, A, A, nb)
+    expect("SQLLM_ERR_NNZ", f, 4, 128, -5, A, A, A, A, nb)
+    f(0, 128, 0, A, None, None, A, 4096, stream=0)                   # nothing to do, nothing enqueued
+    # with a plan the CSR arrays of a one-column call may be NULL; the plan must be aligned
+    g = lambda plan: sq.sqllm_dense_sparse_matvec(0, 128, 3, 5, 1, A, A, None, None, None, A, A, stream=0, plan=plan)
+    g(A)
+    with pytest.raises(sq.SqllmError) as e:
+        sq.sqllm_dense_sparse_matvec(4, 128, 3, 5, 1, A, A, None, None, None, A, A, stream=0, plan=A + 64)
+    assert binding.STATUS_NAMES[e.value.status] == "SQLLM_ERR_ALIGN"
+    with pytest.raises(sq.SqllmError) as e:                          # B = 2 ignores the plan and needs the CSR arrays
+        sq.sqllm_dense_sparse_matvec(4, 128, 3, 5, 2, A, A, None, None, None, A, A, stream=0, plan=A)
+    assert binding.STATUS_NAMES[e.value.status] == "SQLLM_ERR_NULL"
+
+
 def test_debug_and_baseline_argument_errors():
     expect("SQLLM_ERR_NULL", sq.sqllm_unpack_indices, 4, 128, 3, A, None)
     expect("SQLLM_ERR_BITS", sq.sqllm_unpack_indices, 4, 128, 1, A, A)

@@ -1,0 +1,151 @@
+"""The plan of the sparse term (sqllm_csr_plan_build) and the one-column kernel that reads it: the re-layout is checked entry by
+entry against the CSR arrays (integer work: bit-exact), the planned matvec against the CPU oracle to the same bars as the
+unplanned one, on small ragged layers, degenerate sparsity patterns (overflow of heavy rows) and the full benchmark shapes."""
+import numpy as np
+import pytest
+
+import gen
+import oracle
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+SEED = 20230613
+
+
+def layout(M, N, nnz):
+    """the offsets of the plan's sections, as documented with PlanLayout in csrc/sqllm_kernels.h"""
+    W = (N + 2047) // 2048
+    R = 8 if W >= 8 else 4
+    n_wg = (M + R - 1) // R
+    groups = nnz // 16 + M // 2 + 1
+    C = max(1, min(W, (groups * 115 // 100 + 4 * n_wg - 1) // (4 * n_wg)))
+    ov_cap = (nnz // 16 + M) // 4 + n_wg + 1
+    up = lambda v: (v + 255) & ~255
+    off, o = {}, 0
+    for name, size in (("slot_entries", n_wg * C * 256), ("slot_tags", n_wg * C * 4), ("ov_desc", n_wg * 8), ("ov_entries", ov_cap * 256), ("ov_tags", ov_cap * 4)):
+        off[name] = o
+        o += up(size)
+    return R, n_wg, C, ov_cap, off, o
+
+
+def decode_plan(buf, L):
+    """(row, col, fp16 bits) of every valid entry of the plan, workgroup by workgroup, in storage order"""
+    import paper_2306_07629_amd as sq
+    R, n_wg, C, ov_cap, off, total = layout(L.M, L.N, L.nnz)
+    assert total == sq.sqllm_csr_plan_bytes(L.M, L.N, L.nnz) == buf.size
+    se = buf[off["slot_entries"]:off["slot_entries"] + n_wg * C * 256].view(np.uint32).reshape(n_wg, C, 64)
+    st = buf[off["slot_tags"]:off["slot_tags"] + n_wg * C * 4].reshape(n_wg, C, 4)
+    od = buf[off["ov_desc"]:off["ov_desc"] + n_wg * 8].view(np.int32).reshape(n_wg, 2)
+    oe = buf[off["ov_entries"]:off["ov_entries"] + ov_cap * 256].view(np.uint32).reshape(ov_cap, 64)
+    ot = buf[off["ov_tags"]:off["ov_tags"] + ov_cap * 4].reshape(ov_cap, 4)
+    out = []
+    assert od[0, 0] == 0 and (np.diff(od[:, 0]) == od[:-1, 1]).all() and od[-1, 0] + od[-1, 1] <= ov_cap
+    for b in range(n_wg):
+        batches = [(se[b, k], st[b, k]) for k in range(C)] + [(oe[od[b, 0] + k], ot[od[b, 0] + k]) for k in range(od[b, 1])]
+        seen_invalid = False
+        for ent, tags in batches:
+            for gi in range(4):
+                t = int(tags[gi])
+                if not t & 0x80:
+                    seen_invalid = True
+                    assert (ent[16 * gi:16 * gi + 16] == 0).all()
+                    continue
+                assert not seen_invalid, "a valid group after an empty one"
+                row, cnt = b * R + (t & 7), ((t >> 3) & 15) + 1
+                e = ent[16 * gi:16 * gi + cnt]
+                assert (ent[16 * gi + cnt:16 * gi + 16] == 0).all()
+                out.extend((row, int(v & 0x7FFF), int(v >> 16)) for v in e)
+                assert ((e >> 15) & 1 == 0).all()
+    return out
+
+
+CASES = [  # (M, N, bits, frac, skew)
+    (37, 128, 3, 0.02, None), (301, 2176, 4, 0.0045, (0.1, 0.5)), (130, 4096, 3, 0.0045, None), (67, 11008, 3, 0.0045, (0.1, 0.5)),
+    (33, 22016, 3, 0.0045, (0.01, 0.3)), (9, 28672, 2, 0.0045, None), (1, 128, 3, 0.05, None), (5, 16384, 4, 0.01, None), (1030, 4096, 2, 0.001, (0.1, 0.5)),
+]
+
+
+@pytest.mark.parametrize("M,N,bits,frac,skew", CASES)
+def test_plan_holds_exactly_the_csr_entries_and_the_planned_matvec_matches_the_oracle(M, N, bits, frac, skew):
+    import paper_2306_07629_amd as sq
+    print(f"plan case M={M} N={N} bits={bits} frac={frac} skew={skew}", flush=True)
+    L = gen.make_layer(M, N, bits, frac=frac, skew=skew, seed=8000 + M + N + bits)
+    D = sq.DeviceLayer(L).build_plan()
+    got = decode_plan(D.plan.cpu().numpy(), L)
+    rows = np.repeat(np.arange(M), np.diff(L.rowptr))
+    want = list(zip(rows.tolist(), L.cols.tolist(), L.vals.tolist()))
+    assert got == want                                            # same entries, same (row-major, column-ascending) order
+    y_ref, absdot = oracle.layer_matvec(L)
+    y = D.matvec().cpu().numpy().view(np.float16).astype(np.float64)
+    err = np.abs(y - y_ref)
+    assert (err <= TOL * absdot + 2.0 ** -25).all(), float(np.max(err / (TOL * absdot + 2.0 ** -25)))
+    tight = 2.0 ** -11 * np.abs(y_ref) + 2.0 ** -24 + (N + 64) * 2.0 ** -24 * absdot
+    assert (err <= tight).all()
+    # without the plan: the same entry point on the CSR arrays, same tolerance, results equal up to the order of additions
+    D2 = sq.DeviceLayer(L)
+    y2 = D2.matvec().cpu().numpy().view(np.float16).astype(np.float64)
+    assert (np.abs(y - y2) <= 2.0 ** -10 * np.abs(y2) + 2.0 ** -24).all()
+    # run to run
+    a = D.matvec().cpu().numpy().copy()
+    for _ in range(3):
+        assert np.array_equal(D.matvec().cpu().numpy(), a)
+
+
+def test_heavy_rows_overflow_the_slots():
+    """one row holds every column, its neighbour thousands, the rest of the matrix next to nothing: most batches of that
+    workgroup live in the overflow region and are shared by all waves"""
+    import paper_2306_07629_amd as sq
+    M, N, bits = 64, 8192, 3
+    rng = np.random.default_rng(8)
+    idx = rng.integers(0, 8, size=(M, N), dtype=np.uint8)
+    lut = np.sort((rng.standard_normal((M, 8)) * 0.05).astype(np.float16), axis=1)
+    counts = np.zeros(M, dtype=np.int64); counts[17] = N; counts[18] = 5000; counts[19] = 17; counts[40] = 16; counts[41] = 1; counts[63] = 33
+    rowptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    cols = np.concatenate([np.sort(rng.choice(N, c, replace=False)) for c in counts if c]).astype(np.int32)
+    vals = (rng.standard_normal(cols.size) * 0.1).astype(np.float16)
+    x = rng.standard_normal((N, 1)).astype(np.float16)
+    L = gen.hand_layer(idx, lut, bits, rowptr, cols, vals, x)
+    D = sq.DeviceLayer(L).build_plan()
+    got = decode_plan(D.plan.cpu().numpy(), L)
+    rows = np.repeat(np.arange(M), np.diff(L.rowptr))
+    assert got == list(zip(rows.tolist(), L.cols.tolist(), L.vals.tolist()))
+    y_ref, a_ref = oracle.layer_matvec(L)
+    y = D.matvec().cpu().numpy().view(np.float16).astype(np.float64)
+    assert (np.abs(y - y_ref) <= TOL * a_ref).all()
+
+
+@pytest.mark.parametrize("M,N,skew", [(8192, 8192, (0.01, 0.30)), (22016, 8192, (0.01, 0.30)), (8192, 22016, (0.01, 0.30)), (11008, 4096, (0.10, 0.50)),
+                                      (4096, 11008, (0.10, 0.50)), (13824, 5120, None)])
+def test_planned_matvec_at_the_benchmark_shapes(M, N, skew):
+    import paper_2306_07629_amd as sq
+    print(f"planned full size {M}x{N}", flush=True)
+    L = gen.make_layer(M, N, 3, frac=0.0045, skew=skew, seed=gen.layer_seed(SEED, 9, M // 100 + N // 1000))
+    D = sq.DeviceLayer(L).build_plan()
+    y = D.matvec().cpu().numpy().view(np.float16).astype(np.float64)
+    y_ref, absdot = oracle.layer_matvec(L)
+    err = np.abs(y - y_ref)
+    assert np.isfinite(y).all() and (err <= TOL * absdot).all(), float(np.max(err / (TOL * absdot)))
+    assert (err <= 2.0 ** -11 * np.abs(y_ref) + 2.0 ** -24 + (N + 4096) * 2.0 ** -24 * absdot).all()
+
+
+def test_planned_layers_stacked_and_in_one_launch_give_the_bits_of_separate_calls():
+    """q, k, v stacked into one 3 M x N layer, and the three layers in one multi-layer launch: with a plan every row's nonzeros
+    are summed in an order of their own, so even the fused result is bit for bit that of the separate calls"""
+    import torch
+    import paper_2306_07629_amd as sq
+    from test_gpu_stacked_and_unit import stack
+    layers = [gen.make_layer(1024, 4096, 3, frac=0.0045, skew=(0.10, 0.50), seed=gen.layer_seed(SEED, 10, k)) for k in range(3)]
+    for L in layers[1:]:
+        L.x = layers[0].x
+    devs = [sq.DeviceLayer(L).build_plan() for L in layers]
+    sep = [D.matvec().clone() for D in devs]
+    S = stack(layers)
+    DS = sq.DeviceLayer(S).build_plan()
+    ys = DS.matvec()
+    assert torch.equal(ys, torch.cat(sep))
+    for D in devs:
+        D.y.zero_()
+    sq.sqllm_dense_sparse_matvec_multi([D.descriptor() for D in devs])
+    torch.cuda.synchronize()
+    for D, y1 in zip(devs, sep):
+        assert torch.equal(D.y, y1)
