@@ -131,6 +131,23 @@ def bench_quantize(args):
                      "algorithmic_lane_ops_per_launch": ops},
         "cpu_baseline": cpu,
     }
+    if args.workload == "llama65b_mlp_pair_3bit" and not args.no_extras:
+        # the two other headline figures, measured by the same process after the line's own figures are final; a failure here
+        # is reported in place and leaves the line as it is
+        del ring, dev
+        torch.cuda.empty_cache()
+        extras = {}
+        try:
+            extras["llama7b_mlp_pair_3bit"] = extra_matvec_workload(args, "llama7b_mlp_pair_3bit")
+            a2 = argparse.Namespace(**vars(args))
+            a2.workload, a2.steps, a2.warmup, a2.no_cpu_baseline = "llama7b_decode_step_3bit_multi_step", 20, 3, True
+            d = bench_decode_step(a2, emit=False, fp16=False)
+            extras["llama7b_decode_step_3bit_multi_step"] = {"workload": a2.workload, "us_per_token_equivalent": d["value"], "us_per_matvec": d["us_per_matvec"],
+                                                             "effective_gbs": d["effective_gbs"], "roofline_frac": d["roofline"]["frac"],
+                                                             "entry_point": d["config"]["entry_point"], "replay_stats_ms_for_K_steps": d["replay_stats_ms_for_K_steps"]}
+        except (Exception, SystemExit) as e:   # the default line must not depend on the extras
+            extras["error"] = repr(e)
+        out["extras"] = extras
     print(json.dumps(out))
 
 
@@ -158,7 +175,7 @@ DECODE_STEP = {
 }
 
 
-def bench_decode_step(args):
+def bench_decode_step(args, emit=True, fp16=True):
     import numpy as np
     import torch
     import gen
@@ -225,22 +242,24 @@ def bench_decode_step(args):
     gbs = step_bytes * args.steps / sec / 1e9
 
     # fp16 baseline: the same 224 shapes as fp16 matrices (13 GB), library GEMV and the own kernel
-    ws = [(torch.randn(M, N, device="cuda", dtype=torch.float16) * 0.02) for _ in range(blocks) for M, N in shapes]
-    xs = {N: torch.randn(N, device="cuda", dtype=torch.float16) for _, N in shapes}
-    ys = {M: torch.zeros(M, device="cuda", dtype=torch.float16) for M, _ in shapes}
+    us_torch = us_own = None
+    if fp16:
+        ws = [(torch.randn(M, N, device="cuda", dtype=torch.float16) * 0.02) for _ in range(blocks) for M, N in shapes]
+        xs = {N: torch.randn(N, device="cuda", dtype=torch.float16) for _, N in shapes}
+        ys = {M: torch.zeros(M, device="cuda", dtype=torch.float16) for M, _ in shapes}
 
-    def step_torch(_s):
-        for w in ws:
-            torch.mv(w, xs[w.shape[1]], out=ys[w.shape[0]])
+        def step_torch(_s):
+            for w in ws:
+                torch.mv(w, xs[w.shape[1]], out=ys[w.shape[0]])
 
-    def step_own(_s):
-        for w in ws:
-            sq.sqllm_fp16_gemv(w.shape[0], w.shape[1], 1, w, xs[w.shape[1]], ys[w.shape[0]])
+        def step_own(_s):
+            for w in ws:
+                sq.sqllm_fp16_gemv(w.shape[0], w.shape[1], 1, w, xs[w.shape[1]], ys[w.shape[0]])
 
-    fsteps = max(3, args.steps // 4)
-    us_torch = time_steps(torch, step_torch, fsteps, 1, G)[0] / fsteps * 1e6
-    us_own = time_steps(torch, step_own, fsteps, 1, G)[0] / fsteps * 1e6
-    del ws
+        fsteps = max(3, args.steps // 4)
+        us_torch = time_steps(torch, step_torch, fsteps, 1, G)[0] / fsteps * 1e6
+        us_own = time_steps(torch, step_own, fsteps, 1, G)[0] / fsteps * 1e6
+        del ws
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -254,7 +273,7 @@ def bench_decode_step(args):
         cpu = {"value": med * blocks * 1e6, "unit": "us per token-equivalent", "cores": oracle.threads(), "kind": "oracle",
                "sample": f"the {len(kept)} layers of block 0, median of 3 passes, scaled by {blocks} blocks; fp64, OpenMP over rows"}
 
-    print(json.dumps({
+    out = {
         "metric": f"us per token-equivalent: the {n_layers} dense+sparse matvecs ({bits}-bit LUT + {100 * frac:g}% CSR) of the linear layers of a 7B-shaped decode step, back to back on one stream",
         "value": us_step, "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": us_step * 1e-3,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
@@ -264,12 +283,18 @@ def bench_decode_step(args):
                    "entry_point": "sqllm_dense_sparse_matvec_multi, one call per " + ("decoder block" if multi == "multi_block" else "step") if multi else "sqllm_dense_sparse_matvec, one call per layer"},
         "replay_stats_ms_for_K_steps": REPLAY_STATS.get("cold"),
         "us_per_matvec": us_step / n_layers, "effective_gbs": gbs, "pct_of_hbm_roofline": 100.0 * gbs / HBM_PEAK_GBS,
-        "fp16_step_us": {"own_kernel": us_own, "torch_mv": us_torch}, "speedup_vs_fp16": min(us_own, us_torch) / us_step,
+        "fp16_step_us": {"own_kernel": us_own, "torch_mv": us_torch}, "speedup_vs_fp16": min(us_own, us_torch) / us_step if fp16 else None,
         "parity_worst_err_over_bound": worst, "launch_mode": "hip_graph_replay" if G else "python_ctypes", "host_wall_s_timed_region": wall,
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": f"sqllm::matvec_kernel<{bits},1,*>", "algorithmic_bytes_per_launch": step_bytes / n_layers},
+                     "kernel": f"sqllm::matvec{'_planned' if not args.no_plan else ''}{'_multi' if multi else ''}_kernel<{bits},*>",
+                     "algorithmic_bytes_per_launch": step_bytes / n_layers},
         "cpu_baseline": cpu,
-    }))
+    }
+    del dev
+    torch.cuda.empty_cache()
+    if emit:
+        print(json.dumps(out))
+    return out
 
 
 def bench_csr_ablation(args):
@@ -303,9 +328,19 @@ def bench_csr_ablation(args):
                          ("sparse_standard", lambda s: ring[s % copies].csr_spmv(rowwise=True))):
             sec, _ = time_steps(torch, fn, args.steps, args.warmup, not args.no_graph)
             t[name] = sec / args.steps * 1e6
+        # the same fused call with the one-time plan of the sparse term (sqllm_csr_plan_build) in place of the CSR arrays
+        for r in ring:
+            r.build_plan()
+        y = D.matvec().cpu().numpy().view(np.float16).astype(np.float64)
+        if not (np.abs(y - y_ref) <= 2e-3 * absdot).all():
+            print(f"bench.py: parity FAILED in the CSR ablation with a plan ({label})", file=sys.stderr)
+            sys.exit(4)
+        sec, _ = time_steps(torch, lambda s: ring[s % copies].matvec(), args.steps, args.warmup, not args.no_graph)
+        t["fused_planned"] = sec / args.steps * 1e6
         counts = np.diff(L.rowptr)
         rows.append({"skew": label, "max_row_nnz": int(counts.max()), "mean_row_nnz": float(counts.mean()), **{k: round(v, 2) for k, v in t.items()},
                      "sparse_overhead_balanced_pct": round(100 * (t["fused_balanced"] / t["dense_only"] - 1), 1),
+                     "sparse_overhead_planned_pct": round(100 * (t["fused_planned"] / t["dense_only"] - 1), 1),
                      "sparse_overhead_standard_pct": round(100 * (t["dense_then_standard"] / t["dense_only"] - 1), 1)})
         del ring, D
         torch.cuda.empty_cache()
@@ -319,13 +354,14 @@ def bench_csr_ablation(args):
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=64)
-    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--replays", type=int, default=11, help="timed replays of the captured K steps; the median is reported")
     ap.add_argument("--workload", default="llama65b_mlp_pair_3bit", choices=sorted(WORKLOADS) + sorted(QUANT_WORKLOADS) + sorted(CSR_ABLATION) + sorted(DECODE_STEP))
     ap.add_argument("--footprint-gb", type=float, default=1.1, help="bytes of distinct weight copies to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="issue every launch from Python instead of replaying a HIP graph")
+    ap.add_argument("--no-extras", action="store_true", help="default workload only: do not add the 7B MLP pair and the 7B decode step as extra keys")
     ap.add_argument("--no-plan", action="store_true", help="sparse term straight from the CSR arrays instead of from the one-time plan (sqllm_csr_plan_build)")
     return ap.parse_args()
 
@@ -362,7 +398,8 @@ def time_steps(torch, fn, steps, warmup, use_graph=True, replays=11, tag=None):
                 for s in range(steps):
                     fn(warmup + s)
             torch.cuda.synchronize()
-            graph.replay()                       # untimed first replay (uploads the graph)
+            for _ in range(3):                   # untimed replays: the first uploads the graph, the others let the clocks settle
+                graph.replay()
             torch.cuda.synchronize()
             secs, walls = [], []
             for _ in range(max(1, replays)):
@@ -392,6 +429,41 @@ def time_steps(torch, fn, steps, warmup, use_graph=True, replays=11, tag=None):
     return e0.elapsed_time(e1) * 1e-3, wall
 
 
+def extra_matvec_workload(args, name):
+    """cold, graph-replayed us per matvec of another workload of WORKLOADS (parity gate included), for the extras of the default line"""
+    import numpy as np
+    import torch
+    import gen
+    import oracle   # parity gate only
+    import paper_2306_07629_amd as sq
+    shapes, bits, frac, skew, B = WORKLOADS[name]
+    dev, step_bytes = [], 0
+    for li, (M, N) in enumerate(shapes):
+        L = gen.make_layer(M, N, bits, frac=frac, skew=skew, B=B, seed=gen.layer_seed(SEED, 2, li))
+        D = sq.DeviceLayer(L)
+        if not args.no_plan:
+            D.build_plan()
+        y = D.matvec().cpu().numpy().view(np.float16).astype(np.float64)
+        y_ref, absdot = oracle.layer_matvec(L)
+        if not (np.abs(y - y_ref) <= 2e-3 * absdot).all():
+            raise RuntimeError(f"parity failed for {name} layer {M}x{N}")
+        step_bytes += sq.sqllm_algorithmic_bytes(L.M, L.N, L.bits, L.nnz, L.B)
+        dev.append(D)
+    copies = max(2, int(np.ceil(args.footprint_gb * 1e9 / step_bytes)))
+    ring = [[D] + [D.clone_weights() for _ in range(copies - 1)] for D in dev]
+
+    def step(s):
+        for r in ring:
+            r[s % copies].matvec()
+
+    sec, _ = time_steps(torch, step, args.steps, args.warmup, not args.no_graph, args.replays)
+    us = sec / (args.steps * len(shapes)) * 1e6
+    gbs = step_bytes * args.steps / sec / 1e9
+    del ring, dev
+    torch.cuda.empty_cache()
+    return {"workload": name, "us_per_matvec": us, "effective_gbs": gbs, "roofline_frac": gbs / HBM_PEAK_GBS}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -407,15 +479,15 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
     if args.workload in CSR_ABLATION:
-        if args.steps == 64 and args.warmup == 8:
+        if args.steps == 256 and args.warmup == 32:
             args.steps, args.warmup = 200, 20
         return bench_csr_ablation(args)
     if args.workload in DECODE_STEP:
-        if args.steps == 64 and args.warmup == 8:
+        if args.steps == 256 and args.warmup == 32:
             args.steps, args.warmup = 20, 3
         return bench_decode_step(args)
     if args.workload in QUANT_WORKLOADS:
-        if args.steps == 64 and args.warmup == 8:     # the defaults are sized for the microsecond matvecs
+        if args.steps == 256 and args.warmup == 32:     # the defaults are sized for the microsecond matvecs
             args.steps, args.warmup = 20, 3
         return bench_quantize(args)
     shapes, bits, frac, skew, B = WORKLOADS[args.workload]
@@ -554,10 +626,27 @@ def main():
         "device": device_info(torch),
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                      "traffic": traffic,
-                     "kernel": f"sqllm::matvec_kernel<{bits},1,*>" if B == 1 else f"sqllm::matvec_b16_kernel<{bits},*>",
+                     "kernel": (f"sqllm::matvec_kernel<{bits},*>" if args.no_plan else f"sqllm::matvec_planned_kernel<{bits},*>") if B == 1 else f"sqllm::matvec_b16_kernel<{bits},*>",
                      "algorithmic_bytes_per_launch": step_bytes / len(shapes)},
         "cpu_baseline": cpu,
     }
+    if args.workload == "llama65b_mlp_pair_3bit" and not args.no_extras:
+        # the two other headline figures, measured by the same process after the line's own figures are final; a failure here
+        # is reported in place and leaves the line as it is
+        del ring, dev
+        torch.cuda.empty_cache()
+        extras = {}
+        try:
+            extras["llama7b_mlp_pair_3bit"] = extra_matvec_workload(args, "llama7b_mlp_pair_3bit")
+            a2 = argparse.Namespace(**vars(args))
+            a2.workload, a2.steps, a2.warmup, a2.no_cpu_baseline = "llama7b_decode_step_3bit_multi_step", 20, 3, True
+            d = bench_decode_step(a2, emit=False, fp16=False)
+            extras["llama7b_decode_step_3bit_multi_step"] = {"workload": a2.workload, "us_per_token_equivalent": d["value"], "us_per_matvec": d["us_per_matvec"],
+                                                             "effective_gbs": d["effective_gbs"], "roofline_frac": d["roofline"]["frac"],
+                                                             "entry_point": d["config"]["entry_point"], "replay_stats_ms_for_K_steps": d["replay_stats_ms_for_K_steps"]}
+        except (Exception, SystemExit) as e:   # the default line must not depend on the extras
+            extras["error"] = repr(e)
+        out["extras"] = extras
     print(json.dumps(out))
 
 

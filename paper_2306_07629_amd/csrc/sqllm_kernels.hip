@@ -27,6 +27,12 @@
 //     scalar registers, and the products are combined per row with a segmented scan built from DPP moves.
 //     Only the last lane of each row segment touches the row's LDS accumulator, so no floating-point
 //     atomics are needed and the result does not depend on timing.
+//   * With a plan of the sparse term (a one-time re-layout of the CSR arrays, see PlanView) there is no sparse wave: every
+//     dense wave fetches one 64-entry batch of the workgroup's slot at wave start, gathers its activations once its last
+//     index row has been requested, and sums the four 16-entry row groups of the batch with fixed 16-lane reductions.
+//   * matvec_multi_kernel / matvec_planned_multi_kernel run the workgroups of up to eight layers in one grid: a workgroup
+//     finds its layer from the first-block table in the kernel arguments and then runs the same per-block code, so every y
+//     is bit for bit that of a launch of its own.
 // Batches: two to sixteen activation columns go to matvec_b16_kernel, which runs the dense and the sparse term on the
 // matrix cores (every lane decodes its own row, MFMAs replace the packed dot products); its header describes the
 // lane mapping.
