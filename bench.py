@@ -587,7 +587,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic_" + args.workload + ".json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch_no_plan" if args.no_plan else "hbm_bytes_per_launch")
         except Exception:
             traffic = None
 
