@@ -102,7 +102,7 @@ int sqllm_dense_sparse_matvec(int M, int N, int bits, long long nnz, int B,
 
 /* Plan of the sparse term: a one-time re-layout of the CSR arrays of a (static) weight matrix for the one-column kernel
  * (Sec. 4.3 / App. C balance the nonzeros over the threads at run time; weights do not change, so the balancing can be done
- * once).  The nonzeros of every workgroup's rows are stored as groups of 16 entries of one row -- column and fp16 value
+ * once).  The nonzeros of every block of four rows are stored as groups of 16 entries of one row -- column and fp16 value
  * packed into one 32-bit word -- at a position the kernel derives from its workgroup index, with an overflow list for heavy
  * rows.  With a plan the matvec requests its nonzeros at wave start (no row-pointer hop), reads 4 instead of 6 bytes per
  * nonzero (plus the padding of the groups) and sums a row's group with a fixed 16-lane reduction, cheap enough for the dense
@@ -125,10 +125,13 @@ int sqllm_csr_plan_build(int M, int N, long long nnz, const int* rowptr, const i
  *            layout and alignment of the argument of the same name of sqllm_dense_sparse_matvec (B = 1).  All layers of one
  *            call have the same `bits`.  The descriptors are copied into the kernel arguments: the array may be reused or
  *            freed as soon as the call returns.
- * Consecutive layers are merged into launches of up to SQLLM_MAX_LAYERS_PER_LAUNCH layers (a launch ends early where the row
- * width changes between "below 16384" and "16384 and wider", because the two classes run with different rows per workgroup).
- * Each y is bit for bit what a separate sqllm_dense_sparse_matvec call gives; what is saved is the launch gap and the ramp-up
- * and tail of every layer but the last.  The layers of one call must not depend on each other and their y must not overlap.
+ * Consecutive layers are merged into launches of up to SQLLM_MAX_LAYERS_PER_LAUNCH layers.  A launch ends early where a layer
+ * with a plan follows one without (or the reverse) and, among layers without a plan, where the row width changes between "below
+ * 16384" and "16384 and wider" (those two classes run with different rows per workgroup, on which the summation order of their
+ * sparse term depends).  Layers with a plan give the same bits whatever the rows per workgroup, so their launches choose it by
+ * size: eight rows when the launch is many generations of workgroups, else what the layers' own launches would take.
+ * Each y is bit for bit what a separate sqllm_dense_sparse_matvec call with the same arguments gives; what is saved is the launch
+ * gap and the ramp-up and tail of every layer but the last, and in long launches part of the fixed work per row.  The layers of one call must not depend on each other and their y must not overlap.
  * Errors as for sqllm_dense_sparse_matvec, reported for the first offending layer; nothing is enqueued if any layer fails
  * validation.  count == 0 -> SQLLM_OK.                                                                                          */
 typedef struct {

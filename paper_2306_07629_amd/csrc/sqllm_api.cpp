@@ -162,6 +162,9 @@ int sqllm_csr_plan_build(int M, int N, long long nnz, const int* rowptr, const i
     return SQLLM_OK;
 }
 
+// workgroups of eight rows from which a planned multi-layer launch counts as many generations (256 compute units hold about 1800)
+static const long long kManyGenerationsBlocks = 4096;
+
 int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* stream) {
     static_assert(SQLLM_MAX_LAYERS_PER_LAUNCH == sqllm::kMaxLayersPerLaunch, "header and kernels disagree");
     if (count < 0) return fail(SQLLM_ERR_SHAPE, "count = %d is negative", count);
@@ -187,20 +190,30 @@ int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* 
     while (l < count) {
         sqllm::MultiArgs m;
         memset(&m, 0, sizeof m);
-        // a launch holds layers of one class: rows per workgroup, and sparse term from a plan or from the CSR arrays
-        auto cls_of = [](const sqllm_layer& L) { return sqllm::multi_rows_per_workgroup(L.N) * 2 + ((L.plan != nullptr && L.nnz > 0) ? 1 : 0); };
+        // A launch holds layers of one class.  With the sparse term read from the CSR arrays the batches of a workgroup depend on its
+        // rows, so such a layer keeps the rows per workgroup of its single-layer launch (class = that number) and every y stays bit for
+        // bit that of a call of its own.  With a plan y does not depend on the rows per workgroup: all planned layers form one class,
+        // and the launch takes eight rows when it is many generations of workgroups (fewer, longer workgroups amortise their fixed
+        // work; the other layers' workgroups hide their start-up), else what the layers' own launches would take.
+        auto planned_of = [](const sqllm_layer& L) { return L.plan != nullptr && L.nnz > 0; };
+        auto cls_of = [&](const sqllm_layer& L) { return planned_of(L) ? 1 : 2 * sqllm::multi_rows_per_workgroup(L.N); };
         const int cls = cls_of(layers[l]);
+        long long blocks8 = 0;
+        int widest_rule = 4;
         while (l < count && m.count < sqllm::kMaxLayersPerLaunch && cls_of(layers[l]) == cls) {
             const sqllm_layer& L = layers[l];
             if (L.M > 0) {
                 const int k = m.count++;
                 m.M[k] = L.M; m.N[k] = L.N; m.nnz[k] = L.nnz; m.qidx[k] = L.qidx; m.lut[k] = L.lut; m.rowptr[k] = L.rowptr; m.cols[k] = L.cols;
-                m.vals[k] = L.vals; m.x[k] = L.x; m.y[k] = L.y; m.plan[k] = (L.plan != nullptr && L.nnz > 0) ? L.plan : nullptr;
+                m.vals[k] = L.vals; m.x[k] = L.x; m.y[k] = L.y; m.plan[k] = planned_of(L) ? L.plan : nullptr;
+                blocks8 += (L.M + 7) / 8;
+                if (sqllm::multi_rows_per_workgroup(L.N) == 8) widest_rule = 8;
             }
             ++l;
         }
         if (m.count == 0) continue;
-        const hipError_t e = sqllm::launch_matvec_multi(m, layers[0].bits, static_cast<hipStream_t>(stream));
+        const int rows = cls == 1 ? ((blocks8 >= kManyGenerationsBlocks || widest_rule == 8) ? 8 : 4) : cls / 2;
+        const hipError_t e = sqllm::launch_matvec_multi(m, layers[0].bits, rows, static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return hip_fail(e, "multi-layer matvec launch");
     }
     return SQLLM_OK;

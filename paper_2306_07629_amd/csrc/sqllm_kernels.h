@@ -20,16 +20,18 @@ struct MatvecArgs {
     int plan_c;             // slot batches per workgroup of that plan (set by the launcher)
 };
 
-// ---- Plan of the sparse term (built once per matrix, caller-owned device buffer).  The nonzeros of every workgroup's rows are
-// re-laid-out as GROUPS of 16 entries of one row (zero-padded), four groups to a BATCH of 64 lanes:
-//   entry  u32 = column (15 bits) | fp16 value << 16          tag byte of a group = valid << 7 | (count - 1) << 3 | row within the workgroup
-// The first `C` batches of workgroup b sit in a fixed slot (batch b C + k), so the kernel can request them at wave start from its
+// ---- Plan of the sparse term (built once per matrix, caller-owned device buffer).  The nonzeros of every block of four
+// consecutive rows are re-laid-out as GROUPS of 16 entries of one row (zero-padded), four groups to a BATCH of 64 lanes:
+//   entry  u32 = column (15 bits) | fp16 value << 16          tag byte of a group = valid << 7 | (count - 1) << 3 | row within the block
+// The first `C` batches of block b sit in a fixed slot (batch b C + k), so the kernel can request them at wave start from its
 // workgroup index alone; what does not fit (a heavy row) goes to an overflow region described by one (first batch, batches) pair
-// per workgroup.  Every offset below follows from (M, N, nnz) alone, so the host never has to read the plan.
+// per block.  Every offset below follows from (M, N, nnz) alone, so the host never has to read the plan.  The block size does
+// not depend on the rows per workgroup of the kernel: a workgroup of eight rows serves two blocks, each in the order a workgroup
+// of four would, so y does not depend on that choice.
 struct PlanLayout {
-    int R;                      // rows per workgroup of the one-column kernel for this row width (4 or 8)
-    int n_wg;                   // workgroups = ceil(M / R)
-    int C;                      // slot batches per workgroup
+    int R;                      // rows per block (4)
+    int n_wg;                   // blocks = ceil(M / R)
+    int C;                      // slot batches per block
     long long ov_cap;           // capacity of the overflow region in batches
     size_t off_slot_entries, off_slot_tags, off_ov_desc, off_ov_entries, off_ov_tags, bytes;
 };
@@ -54,7 +56,7 @@ struct MultiArgs {
     int plan_c[kMaxLayersPerLaunch];            // filled by the launcher
 };
 int multi_rows_per_workgroup(int N);             // rows per workgroup of the one-column kernel for rows of N columns (4 or 8)
-hipError_t launch_matvec_multi(MultiArgs& m, int bits, hipStream_t s);
+hipError_t launch_matvec_multi(MultiArgs& m, int bits, int rows_per_workgroup, hipStream_t s);
 
 // Offline side (sqllm_quant.hip): everything is a caller-owned device pointer.
 struct QuantArgs {

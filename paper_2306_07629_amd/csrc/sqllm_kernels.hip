@@ -492,33 +492,36 @@ __device__ __forceinline__ void matvec_block(const MatvecArgs& g, int block, int
 }
 
 // ---------------------------------------------------------------------------------------------- sparse term from a plan
-// A plan (sqllm_kernels.h: PlanLayout) holds the nonzeros of every workgroup's rows as groups of 16 entries of one row, four
-// groups to a batch of 64 lanes, the first C batches of a workgroup in a slot found from the workgroup index alone.  Against the
+// A plan (sqllm_kernels.h: PlanLayout) holds the nonzeros of every block of four rows (a "quad") as groups of 16 entries of one
+// row, four groups to a batch of 64 lanes, the first C batches of a quad in a slot found from the quad index alone.  A workgroup
+// of R rows serves R / 4 quads, each exactly as a four-row workgroup would (same batches on the same waves in the same order),
+// so the sparse sums -- like the dense ones -- do not depend on R.  Against the
 // CSR arrays this removes the first hop of the dependent chain (row pointers -> columns / values -> gathers), halves the loads
 // per nonzero (column and value share a dword) and replaces the segmented scan by a fixed 16-lane reduction -- cheap enough for
 // the dense waves to carry the sparse term themselves, so a workgroup needs no extra wave.
 struct PlanView {
-    const u32* slot_entries;    // [n_wg][C][64]
-    const uint8_t* slot_tags;   // [n_wg][C][4]   one tag byte per group
-    const int* ov_desc;         // [n_wg][2]      first overflow batch, overflow batches
+    const u32* slot_entries;    // [quads][C][64]
+    const uint8_t* slot_tags;   // [quads][C][4]  one tag byte per group
+    const int* ov_desc;         // [quads][2]     first overflow batch, overflow batches
     const u32* ov_entries;      // [ov batches][64]
     const uint8_t* ov_tags;     // [ov batches][4]
     int C;
     int ov_cap;                 // batches the overflow sections hold
 };
 
-template <int R>
+constexpr int kPlanRows = 4;   // rows of a plan block ("quad"), whatever the rows per workgroup of the kernel that reads it
+
 __device__ __forceinline__ PlanView plan_view(const void* plan, int M, long long nnz, int C) {
     // the offsets of plan_layout() on the host; C comes with the kernel arguments (its formula needs a 64-bit division)
-    const size_t n_wg = (size_t)((M + R - 1) / R);
-    const size_t ov_cap = (size_t)((nnz / 16 + M) / 4) + n_wg + 1;
+    const size_t n_q = (size_t)((M + kPlanRows - 1) / kPlanRows);
+    const size_t ov_cap = (size_t)((nnz / 16 + M) / 4) + n_q + 1;
     auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
     const char* b = static_cast<const char*>(plan);
     PlanView v;
     size_t o = 0;
-    v.slot_entries = reinterpret_cast<const u32*>(b + o); o += up(n_wg * C * 256);
-    v.slot_tags = reinterpret_cast<const uint8_t*>(b + o); o += up(n_wg * C * 4);
-    v.ov_desc = reinterpret_cast<const int*>(b + o);      o += up(n_wg * 8);
+    v.slot_entries = reinterpret_cast<const u32*>(b + o); o += up(n_q * C * 256);
+    v.slot_tags = reinterpret_cast<const uint8_t*>(b + o); o += up(n_q * C * 4);
+    v.ov_desc = reinterpret_cast<const int*>(b + o);      o += up(n_q * 8);
     v.ov_entries = reinterpret_cast<const u32*>(b + o);   o += up(ov_cap * 256);
     v.ov_tags = reinterpret_cast<const uint8_t*>(b + o);
     v.C = C;
@@ -552,8 +555,8 @@ __device__ __forceinline__ void matvec_planned_block(const MatvecArgs& g, int bl
     static_assert(D >= 2 && D <= R && (R == 4 || R == 8), "prefetch depth, rows per workgroup");
     constexpr int K = 1 << BITS;
     constexpr int kRawUnit = TableShape<BITS>::kRawUnit;
-    constexpr int UE = 1;                                            // slot batches per wave (C <= UE W)
-    constexpr int UP = 2;                                            // overflow batches per wave requested ahead
+    constexpr int Q = R / kPlanRows;                                 // quads of the plan per workgroup; C <= W: one slot batch per wave and quad
+    constexpr int UP = Q == 1 ? 2 : 1;                               // overflow batches per wave and quad requested ahead
     constexpr int TD = TableShape<BITS>::kTableDwords;
     __shared__ __align__(8) u32 tables[R * TD];
     __shared__ __align__(16) uint16_t raw[R * K];
@@ -564,7 +567,8 @@ __device__ __forceinline__ void matvec_planned_block(const MatvecArgs& g, int bl
     const int r0 = block * R;
     const int nrows = min(R, g.M - r0);
     const uint16_t* __restrict__ x = static_cast<const uint16_t*>(g.x);
-    const PlanView pv = plan_view<R>(g.plan, g.M, g.nnz, g.plan_c);
+    const PlanView pv = plan_view(g.plan, g.M, g.nnz, g.plan_c);
+    const int n_quads = (g.M + kPlanRows - 1) / kPlanRows;
     float* myslots = spart + wave * R;
     if (lane < R) myslots[lane] = 0.f;
 
@@ -593,19 +597,20 @@ __device__ __forceinline__ void matvec_planned_block(const MatvecArgs& g, int bl
     LaneChunk<BITS> c[R];
 #pragma unroll
     for (int u = 0; u < D; ++u) c[u] = load_chunk<BITS>(qlane + (size_t)min(r0 + u, g.M - 1) * row_dwords);
-    // Slot batch k of this wave is batch wave + k W of the workgroup's slot; past the slot (>= C) the last batch is re-read and its
-    // tags are cleared.  Entries, tag bytes (one per group, fetched by the group's own lanes) and the overflow descriptor all come
-    // through vector loads: a scalar load would have to be waited for together with every LDS operation of the wave.
-    u32 ent[UE], tags[UE], sx[UE], oe[UP], ot[UP];
-    int ov_first = 0, ov_nb = 0;
+    // The slot batch of this wave in quad q is batch `wave` of that quad's slot; past the slot (wave >= C) the last batch is
+    // re-read and ignored.  Entries, tag bytes (one per group, fetched by the group's own lanes) and the overflow descriptors all
+    // come through vector loads: a scalar load would have to be waited for together with every LDS operation of the wave.
+    u32 ent[Q], tags[Q], sx[Q], oe[Q][UP], ot[Q][UP];
+    int ovd[Q], ov_first[Q], ov_nb[Q];
 #pragma unroll
-    for (int k = 0; k < UE; ++k) {
-        const int kb = min(wave + k * W, pv.C - 1);
-        const size_t sb = (size_t)block * pv.C + kb;
-        ent[k] = pv.slot_entries[sb * 64 + lane];
-        tags[k] = pv.slot_tags[sb * 4 + (lane >> 4)];
+    for (int q = 0; q < Q; ++q) {
+        const int quad = min(block * Q + q, n_quads - 1);            // a workgroup at the end of M may have no second quad
+        const size_t sb = (size_t)quad * pv.C + min(wave, pv.C - 1);
+        ent[q] = pv.slot_entries[sb * 64 + lane];
+        tags[q] = pv.slot_tags[sb * 4 + (lane >> 4)];
+        ovd[q] = pv.ov_desc[2 * quad + (lane & 1)];                  // lane 0: first overflow batch, lane 1: their number
+        ov_first[q] = 0; ov_nb[q] = 0;
     }
-    const int ovd = pv.ov_desc[2 * block + (lane & 1)];              // lane 0: first overflow batch, lane 1: their number
     if (!live) {
 #pragma unroll
         for (int p = 0; p < 16; ++p) xr[p] = 0;
@@ -640,14 +645,17 @@ __device__ __forceinline__ void matvec_planned_block(const MatvecArgs& g, int bl
         if (u + 1 + D == R - 1 || (D == R - 1 && u == 0)) {
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int k = 0; k < UE; ++k) sx[k] = x[ent[k] & 0x7FFFu];
-            ov_first = __builtin_amdgcn_readlane(ovd, 0);
-            ov_nb = __builtin_amdgcn_readlane(ovd, 1);
+            for (int q = 0; q < Q; ++q) sx[q] = x[ent[q] & 0x7FFFu];
 #pragma unroll
-            for (int k = 0; k < UP; ++k) {
-                const int b = min(ov_first + min(wave + k * W, max(ov_nb - 1, 0)), pv.ov_cap - 1);
-                oe[k] = pv.ov_entries[(size_t)b * 64 + lane];
-                ot[k] = pv.ov_tags[(size_t)b * 4 + (lane >> 4)];
+            for (int q = 0; q < Q; ++q) {
+                ov_first[q] = __builtin_amdgcn_readlane(ovd[q], 0);
+                ov_nb[q] = __builtin_amdgcn_readlane(ovd[q], 1);
+#pragma unroll
+                for (int k = 0; k < UP; ++k) {
+                    const int b = min(ov_first[q] + min(wave + k * W, max(ov_nb[q] - 1, 0)), pv.ov_cap - 1);
+                    oe[q][k] = pv.ov_entries[(size_t)b * 64 + lane];
+                    ot[q][k] = pv.ov_tags[(size_t)b * 4 + (lane >> 4)];
+                }
             }
         }
         acc[u] = dot_chunk(w[u & 1], xr);
@@ -663,34 +671,39 @@ __device__ __forceinline__ void matvec_planned_block(const MatvecArgs& g, int bl
     }
     row_block_reduce<R>(acc, lane);
     if (row_block_valid(lane) && (R == 8 || !(lane & 8))) part[(wave * 4 + (lane >> 4)) * R + row_block_class<R>(lane)] = acc[0];
-    // ---- sparse term: this wave's slot batches, then its share of the overflow batches
+    // ---- sparse term, quad by quad: this wave's slot batch, then its share of the quad's overflow batches (batches wave, wave + W,
+    // wave + 2 W, ... in this order whatever UP and R are)
+    constexpr int UO = 8;                                            // batches per wave and round in the loop for very heavy rows
 #pragma unroll
-    for (int k = 0; k < UE; ++k)
-        if (wave + k * W < pv.C) plan_batch_reduce(ent[k], sx[k], tags[k], lane, myslots);    // uniform
-    if (wave < ov_nb) {                                                                       // uniform
-        u32 ox[UP];
+    for (int q = 0; q < Q; ++q) {
+        float* qslots = myslots + q * kPlanRows;
+        const bool have = block * Q + q < n_quads;                   // uniform; the last workgroup of an odd number of quads has one
+        const int nb = have ? ov_nb[q] : 0, first = ov_first[q];
+        if (wave < pv.C && have) plan_batch_reduce(ent[q], sx[q], tags[q], lane, qslots);     // uniform
+        if (wave < nb) {                                                                      // uniform
+            u32 ox[UP];
 #pragma unroll
-        for (int k = 0; k < UP; ++k) ox[k] = x[oe[k] & 0x7FFFu];
+            for (int k = 0; k < UP; ++k) ox[k] = x[oe[q][k] & 0x7FFFu];
 #pragma unroll
-        for (int k = 0; k < UP; ++k)
-            if (wave + k * W < ov_nb) plan_batch_reduce(oe[k], ox[k], ot[k], lane, myslots);
-    }
-    // what a very heavy row leaves after that: UO batches per wave and round, all requested before the first is used (the
-    // workgroup that owns such a row ends last, and every round costs it two memory latencies)
-    constexpr int UO = 8;
-    for (int ob = wave + UP * W; ob < ov_nb; ob += UO * W) {                                  // uniform
-        u32 e2[UO], t2[UO], x2[UO];
-#pragma unroll
-        for (int k = 0; k < UO; ++k) {
-            const int b = min(ob + k * W, ov_nb - 1);
-            e2[k] = pv.ov_entries[(size_t)(ov_first + b) * 64 + lane];
-            t2[k] = pv.ov_tags[(size_t)(ov_first + b) * 4 + (lane >> 4)];
+            for (int k = 0; k < UP; ++k)
+                if (wave + k * W < nb) plan_batch_reduce(oe[q][k], ox[k], ot[q][k], lane, qslots);
         }
+        // what a very heavy row leaves after that: UO batches per wave and round, all requested before the first is used (the
+        // workgroup that owns such a row ends last, and every round costs it two memory latencies)
+        for (int ob = wave + UP * W; ob < nb; ob += UO * W) {                                 // uniform
+            u32 e2[UO], t2[UO], x2[UO];
 #pragma unroll
-        for (int k = 0; k < UO; ++k) x2[k] = x[e2[k] & 0x7FFFu];
+            for (int k = 0; k < UO; ++k) {
+                const int b = min(ob + k * W, nb - 1);
+                e2[k] = pv.ov_entries[(size_t)(first + b) * 64 + lane];
+                t2[k] = pv.ov_tags[(size_t)(first + b) * 4 + (lane >> 4)];
+            }
 #pragma unroll
-        for (int k = 0; k < UO; ++k)
-            if (ob + k * W < ov_nb) plan_batch_reduce(e2[k], x2[k], t2[k], lane, myslots);
+            for (int k = 0; k < UO; ++k) x2[k] = x[e2[k] & 0x7FFFu];
+#pragma unroll
+            for (int k = 0; k < UO; ++k)
+                if (ob + k * W < nb) plan_batch_reduce(e2[k], x2[k], t2[k], lane, qslots);
+        }
     }
     __syncthreads();
     uint16_t* __restrict__ y = static_cast<uint16_t*>(g.y);
@@ -1400,12 +1413,12 @@ static hipError_t launch_matvec_one(const MatvecArgs& g, hipStream_t s) {
 
 PlanLayout plan_layout(int M, int N, long long nnz) {
     PlanLayout L;
-    L.R = multi_rows_per_workgroup(N);
+    L.R = kPlanRows;                                                // blocks of four rows, whatever the kernel's rows per workgroup
     L.n_wg = (M + L.R - 1) / L.R;
     const long long n_wg = L.n_wg;
     const long long groups = nnz / 16 + M / 2 + 1;                  // a row of c nonzeros has ceil(c / 16) groups
     const int W = (N + kSliceCols - 1) / kSliceCols;
-    long long C = n_wg > 0 ? (groups * 115 / 100 + 4 * n_wg - 1) / (4 * n_wg) : 1;   // 15 % above the mean; a wave carries at most two slot batches
+    long long C = n_wg > 0 ? (groups * 115 / 100 + 4 * n_wg - 1) / (4 * n_wg) : 1;   // 15 % above the mean; a wave carries at most one slot batch per block
     L.C = (int)(C < 1 ? 1 : (C > W ? W : C));
     L.ov_cap = (nnz / 16 + M) / 4 + n_wg + 1;
     auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
@@ -1429,11 +1442,9 @@ hipError_t launch_plan_build(int M, int N, long long nnz, const int* rowptr, con
     u32* ov_entries = reinterpret_cast<u32*>(b + L.off_ov_entries);
     uint8_t* ov_tags = reinterpret_cast<uint8_t*>(b + L.off_ov_tags);
     const uint16_t* v16 = static_cast<const uint16_t*>(vals);
-    if (L.R == 8) hipLaunchKernelGGL((plan_count_kernel<8>), dim3((L.n_wg + 255) / 256), dim3(256), 0, s, M, L.n_wg, L.C, rowptr, ov_desc);
-    else hipLaunchKernelGGL((plan_count_kernel<4>), dim3((L.n_wg + 255) / 256), dim3(256), 0, s, M, L.n_wg, L.C, rowptr, ov_desc);
+    hipLaunchKernelGGL((plan_count_kernel<kPlanRows>), dim3((L.n_wg + 255) / 256), dim3(256), 0, s, M, L.n_wg, L.C, rowptr, ov_desc);
     hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, s, L.n_wg, ov_desc);
-    if (L.R == 8) hipLaunchKernelGGL((plan_fill_kernel<8>), dim3(L.n_wg), dim3(64), 0, s, M, L.C, rowptr, cols, v16, slot_entries, slot_tags, ov_desc, ov_entries, ov_tags);
-    else hipLaunchKernelGGL((plan_fill_kernel<4>), dim3(L.n_wg), dim3(64), 0, s, M, L.C, rowptr, cols, v16, slot_entries, slot_tags, ov_desc, ov_entries, ov_tags);
+    hipLaunchKernelGGL((plan_fill_kernel<kPlanRows>), dim3(L.n_wg), dim3(64), 0, s, M, L.C, rowptr, cols, v16, slot_entries, slot_tags, ov_desc, ov_entries, ov_tags);
     return hipGetLastError();
 }
 
@@ -1472,8 +1483,7 @@ static hipError_t launch_multi_r(MultiArgs& m, hipStream_t s) {
 
 int multi_rows_per_workgroup(int N) { return (N + kSliceCols - 1) / kSliceCols >= 8 ? 8 : 4; }
 
-hipError_t launch_matvec_multi(MultiArgs& m, int bits, hipStream_t s) {
-    const int R = multi_rows_per_workgroup(m.N[0]);                 // the caller groups layers of one class into a launch
+hipError_t launch_matvec_multi(MultiArgs& m, int bits, int R, hipStream_t s) {
     if (R == 8) return bits == 2 ? launch_multi_r<2, 8>(m, s) : (bits == 3 ? launch_multi_r<3, 8>(m, s) : launch_multi_r<4, 8>(m, s));
     return bits == 2 ? launch_multi_r<2, 4>(m, s) : (bits == 3 ? launch_multi_r<3, 4>(m, s) : launch_multi_r<4, 4>(m, s));
 }

@@ -15,7 +15,7 @@ SEED = 20230613
 def layout(M, N, nnz):
     """the offsets of the plan's sections, as documented with PlanLayout in csrc/sqllm_kernels.h"""
     W = (N + 2047) // 2048
-    R = 8 if W >= 8 else 4
+    R = 4                                                          # rows per block of the plan, whatever the kernel's rows per workgroup
     n_wg = (M + R - 1) // R
     groups = nnz // 16 + M // 2 + 1
     C = max(1, min(W, (groups * 115 // 100 + 4 * n_wg - 1) // (4 * n_wg)))
@@ -149,3 +149,41 @@ def test_planned_layers_stacked_and_in_one_launch_give_the_bits_of_separate_call
     torch.cuda.synchronize()
     for D, y1 in zip(devs, sep):
         assert torch.equal(D.y, y1)
+
+
+def planned_multi_equals_separate(specs, bits, seed0):
+    import torch
+    import paper_2306_07629_amd as sq
+    layers = [gen.make_layer(M, N, bits, frac=frac, skew=skew, seed=seed0 + k) for k, (M, N, frac, skew) in enumerate(specs)]
+    devs = [sq.DeviceLayer(L).build_plan() for L in layers]
+    sep = []
+    for D in devs:
+        sep.append(D.matvec().clone())                              # four rows per workgroup for rows below 16384 columns
+        D.y.fill_(0x7BFF)
+    torch.cuda.synchronize()
+    sq.sqllm_dense_sparse_matvec_multi([D.descriptor() for D in devs])
+    torch.cuda.synchronize()
+    for k, (L, D, y1) in enumerate(zip(layers, devs, sep)):
+        assert torch.equal(D.y, y1), f"layer {k} ({L.M}x{L.N}) differs from the separate call"
+        y_ref, absdot = oracle.layer_matvec(L)
+        err = np.abs(D.y.cpu().numpy().view(np.float16).astype(np.float64) - y_ref)
+        assert (err <= TOL * absdot + 2.0 ** -25).all(), f"layer {k}"
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_planned_multi_launch_with_eight_rows_per_workgroup_gives_the_bits_of_the_four_row_launches(bits):
+    """A 16384-wide layer makes the whole planned launch run with eight rows per workgroup, i.e. two plan blocks per workgroup;
+    the narrow layers' own launches use four.  Row counts that leave the last workgroup one block, or a block of one to three rows;
+    layers without nonzeros (no plan: they go to a launch of their own class); heavy rows that overflow the slot."""
+    specs = [(33, 16384, 0.0045, None), (37, 128, 0.02, None), (301, 2176, 0.0045, (0.1, 0.5)), (4, 4096, 0.01, None), (12, 8192, 0.0045, None),
+             (64, 128, 0.0, None), (203, 1024, 0.0045, (0.01, 0.3)), (1, 128, 0.05, None), (70, 11008, 0.0045, (0.1, 0.5)), (5, 2048, 0.3, None)]
+    print(f"planned multi, eight rows, {bits}-bit", flush=True)
+    planned_multi_equals_separate(specs, bits, 8800 + bits)
+
+
+def test_planned_multi_launch_of_many_workgroups_switches_to_eight_rows_and_keeps_the_bits():
+    """three 11008x4096 and two 4096x4096 layers: more than 4096 eight-row workgroups, so the launch takes eight rows per
+    workgroup where the single-layer launches take four"""
+    specs = [(11008, 4096, 0.0045, (0.1, 0.5))] * 3 + [(4096, 4096, 0.0045, (0.1, 0.5))] * 2
+    print("planned multi, full size", flush=True)
+    planned_multi_equals_separate(specs, 3, 8900)

@@ -120,56 +120,59 @@ def sixteen_column_kernel_reads(M, N, bits, B, rowptr):
 
 
 def plan_sections(M, N, nnz):
-    """sizes in bytes of the five sections of a plan (the layout documented with PlanLayout in csrc/sqllm_kernels.h)"""
+    """sizes in bytes of the five sections of a plan (the layout documented with PlanLayout in csrc/sqllm_kernels.h): blocks of four
+    rows whatever the rows per workgroup of the kernel"""
     W = (N + SLICE - 1) // SLICE
-    R = 8 if W >= 8 else 4
-    n_wg = (M + R - 1) // R
+    n_q = (M + 3) // 4
     groups = nnz // 16 + M // 2 + 1
-    C = max(1, min(W, (groups * 115 // 100 + 4 * n_wg - 1) // (4 * n_wg)))
-    ov_cap = (nnz // 16 + M) // 4 + n_wg + 1
-    return R, W, n_wg, C, ov_cap, {"slot_entries": n_wg * C * 256, "slot_tags": n_wg * C * 4, "ov_desc": n_wg * 8, "ov_entries": ov_cap * 256, "ov_tags": ov_cap * 4}
+    C = max(1, min(W, (groups * 115 // 100 + 4 * n_q - 1) // (4 * n_q)))
+    ov_cap = (nnz // 16 + M) // 4 + n_q + 1
+    return W, n_q, C, ov_cap, {"slot_entries": n_q * C * 256, "slot_tags": n_q * C * 4, "ov_desc": n_q * 8, "ov_entries": ov_cap * 256, "ov_tags": ov_cap * 4}
 
 
-def planned_kernel_reads(M, N, rowptr):
-    """every load the planned one-column kernel issues into the plan: the slot batch of each wave, the overflow descriptor, the
-    overflow batches requested ahead (clamped into the overflow sections whatever the descriptor holds) and those of the loop"""
+def planned_kernel_reads(M, N, rowptr, R):
+    """every load the planned one-column kernel with R rows per workgroup issues into the plan: per block of four rows the slot batch
+    of each wave, the overflow descriptor, the overflow batches requested ahead (clamped into the overflow sections whatever the
+    descriptor holds) and those of the loop"""
     nnz = int(rowptr[-1])
-    R, W, n_wg, C, ov_cap, size = plan_sections(M, N, nnz)
+    W, n_q, C, ov_cap, size = plan_sections(M, N, nnz)
     counts = np.diff(rowptr)
-    groups = np.add.reduceat((np.concatenate([counts, np.zeros(n_wg * R - M, dtype=counts.dtype)]) + 15) // 16, np.arange(0, n_wg * R, R))
+    groups = np.add.reduceat((np.concatenate([counts, np.zeros(n_q * 4 - M, dtype=counts.dtype)]) + 15) // 16, np.arange(0, n_q * 4, 4))
     ov_nb = (np.maximum(groups - 4 * C, 0) + 3) // 4
     ov_first = np.concatenate([[0], np.cumsum(ov_nb)[:-1]])
     assert int(ov_first[-1] + ov_nb[-1]) <= ov_cap                # the capacity bound the layout promises
-    lanes = np.arange(WAVE)
-    UP, UO = 2, 8
-    for block in sorted({0, n_wg - 1, n_wg // 2, int(np.argmax(ov_nb))}):
+    Q = R // 4
+    UP, UO = (2 if Q == 1 else 1), 8
+    n_wg = (M + R - 1) // R
+    heavy = int(np.argmax(ov_nb)) // Q
+    for block in sorted({0, n_wg - 1, n_wg // 2, heavy}):
         for wave in range(W):
-            sb = block * C + min(wave, C - 1)
-            yield "slot_entries", sb * 256, sb * 256 + 256
-            yield "slot_tags", sb * 4, sb * 4 + 4
-            yield "ov_desc", 8 * block, 8 * block + 8
-            first, nb = int(ov_first[block]), int(ov_nb[block])
-            for k in range(UP):
-                b = min(first + min(wave + k * W, max(nb - 1, 0)), ov_cap - 1)
-                assert b >= 0
-                yield "ov_entries", b * 256, b * 256 + 256
-                yield "ov_tags", b * 4, b * 4 + 4
-            ob = wave + UP * W
-            while ob < nb:
-                for k in range(UO):
-                    b = first + min(ob + k * W, nb - 1)
+            for q in range(Q):
+                quad = min(block * Q + q, n_q - 1)
+                sb = quad * C + min(wave, C - 1)
+                yield "slot_entries", sb * 256, sb * 256 + 256
+                yield "slot_tags", sb * 4, sb * 4 + 4
+                yield "ov_desc", 8 * quad, 8 * quad + 8
+                first, nb = int(ov_first[quad]), (int(ov_nb[quad]) if block * Q + q < n_q else 0)
+                for k in range(UP):
+                    b = min(first + min(wave + k * W, max(nb - 1, 0)), ov_cap - 1)
+                    assert b >= 0
                     yield "ov_entries", b * 256, b * 256 + 256
                     yield "ov_tags", b * 4, b * 4 + 4
-                ob += UO * W
-    yield "sizes", 0, 0
-    return size
+                ob = wave + UP * W
+                while ob < nb:
+                    for k in range(UO):
+                        b = first + min(ob + k * W, nb - 1)
+                        yield "ov_entries", b * 256, b * 256 + 256
+                        yield "ov_tags", b * 4, b * 4 + 4
+                    ob += UO * W
 
 
 @pytest.mark.parametrize("M,N,bits,B", [s for s in SHAPES if s[3] == 1])
 def test_every_load_of_the_planned_kernel_stays_inside_its_section(M, N, bits, B):
     rowptr = rowptr_for(M, N, M + N + bits)
-    size = plan_sections(M, N, int(rowptr[-1]))[5]
-    reads = [r for r in planned_kernel_reads(M, N, rowptr) if r[0] != "sizes"]
+    size = plan_sections(M, N, int(rowptr[-1]))[4]
+    reads = list(planned_kernel_reads(M, N, rowptr, 4)) + list(planned_kernel_reads(M, N, rowptr, 8))   # either may be launched
     assert len(reads) > 4
     for name, lo, hi in reads:
         assert 0 <= lo and hi <= size[name], (name, lo, hi, size[name])
@@ -179,7 +182,7 @@ def test_plan_sections_add_up_to_the_size_the_library_reports():
     import paper_2306_07629_amd as sq
     for M, N, bits, B in SHAPES:
         nnz = int(rowptr_for(M, N, M + N + bits)[-1])
-        size = plan_sections(M, N, nnz)[5]
+        size = plan_sections(M, N, nnz)[4]
         assert sum((v + 255) & ~255 for v in size.values()) == sq.sqllm_csr_plan_bytes(M, N, nnz)
 
 
