@@ -187,3 +187,11 @@ def test_planned_multi_launch_of_many_workgroups_switches_to_eight_rows_and_keep
     specs = [(11008, 4096, 0.0045, (0.1, 0.5))] * 3 + [(4096, 4096, 0.0045, (0.1, 0.5))] * 2
     print("planned multi, full size", flush=True)
     planned_multi_equals_separate(specs, 3, 8900)
+
+
+def test_four_full_size_decoder_blocks_in_one_call():
+    """28 full-size layers of a 7B-shaped model (four decoder blocks, a seed per layer) in ONE multi-layer call: launches of eight
+    layers with eight rows per workgroup; every y against the oracle and against the layer's own launch"""
+    block = [(4096, 4096, 0.0045, (0.1, 0.5))] * 4 + [(11008, 4096, 0.0045, (0.1, 0.5))] * 2 + [(4096, 11008, 0.0045, (0.1, 0.5))]
+    print("planned multi, four decoder blocks", flush=True)
+    planned_multi_equals_separate(block * 4, 3, 9000)
