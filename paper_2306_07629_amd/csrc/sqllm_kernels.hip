@@ -104,6 +104,17 @@ __device__ __forceinline__ LaneChunk<BITS> load_chunk(const u32* __restrict__ p)
     return c;
 }
 
+// the same from a uniform row pointer and the lane's dword offset inside the row: the address is formed by the load instruction
+// (scalar base + 32-bit vector offset) instead of 64-bit vector arithmetic
+template <int BITS>
+__device__ __forceinline__ LaneChunk<BITS> load_chunk_at(const u32* __restrict__ row, u32 lane_dword) {
+    LaneChunk<BITS> c;
+    const u32* p = reinterpret_cast<const u32*>(reinterpret_cast<const char*>(row) + (size_t)(lane_dword * 4u));
+#pragma unroll
+    for (int k = 0; k < BITS; ++k) c.q[k] = __builtin_nontemporal_load(p + k);
+    return c;
+}
+
 // Byte offsets (entry * 4) into the row's pair table of the 16 index pairs of a lane.
 //   b = 3: pair p owns bits [6p, 6p + 6) of the 96-bit chunk; two of them straddle a dword boundary.
 //   b = 4: pair p is byte p of the 128-bit chunk.
@@ -156,8 +167,8 @@ __device__ __forceinline__ void build_tables(u32* __restrict__ tables, const uin
 
 // ---------------------------------------------------------------------------------------------- x in registers
 // xr[p] = (x[j0 + 2p], x[j0 + 2p + 1]) for the lane's 32 columns j0 .. j0 + 31 (j0 is in range, x is one column).
-__device__ __forceinline__ void load_x(const uint16_t* __restrict__ x, int j0, u32 (&xr)[16]) {
-    const u32x4* src = reinterpret_cast<const u32x4*>(x + j0);
+__device__ __forceinline__ void load_x(const uint16_t* __restrict__ x, u32 j0, u32 (&xr)[16]) {
+    const u32x4* src = reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(x) + (size_t)(j0 * 2u));
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const u32x4 v = src[k];
@@ -394,16 +405,21 @@ __device__ __forceinline__ void matvec_block(const MatvecArgs& g, int block, int
                 rawv.x = v.x; rawv.y = v.y;
             }
         }
-        const int j0 = wave * kSliceCols + lane * kLaneElems;
-        const bool live = j0 < g.N;
-        const int j0c = live ? j0 : g.N - kLaneElems;
+        const u32 j0 = (u32)wave * kSliceCols + (u32)lane * kLaneElems;
+        const bool live = j0 < (u32)g.N;
+        const u32 j0c = live ? j0 : (u32)g.N - kLaneElems;
         u32 xr[16];
         load_x(x, j0c, xr);
         const size_t row_dwords = (size_t)g.N * BITS / 32;
-        const u32* __restrict__ qlane = static_cast<const u32*>(g.qidx) + (size_t)(j0c / 32) * BITS;
+        const u32 lane_dword = (j0c >> 5) * BITS;                    // the lane's 32 indices inside a row of the index stream
+        const u32* __restrict__ qrow0 = static_cast<const u32*>(g.qidx);
+        auto row_ptr = [&](int u) {
+            const u32 row = (u32)__builtin_amdgcn_readfirstlane(min(r0 + u, g.M - 1));   // uniform: the 64-bit product stays on the scalar unit
+            return qrow0 + (size_t)row * row_dwords;
+        };
         LaneChunk<BITS> c[R];
 #pragma unroll
-        for (int u = 0; u < D; ++u) c[u] = load_chunk<BITS>(qlane + (size_t)min(r0 + u, g.M - 1) * row_dwords);
+        for (int u = 0; u < D; ++u) c[u] = load_chunk_at<BITS>(row_ptr(u), lane_dword);
         if (!live) {
 #pragma unroll
             for (int p = 0; p < 16; ++p) xr[p] = 0;
@@ -424,12 +440,12 @@ __device__ __forceinline__ void matvec_block(const MatvecArgs& g, int block, int
         float acc[R];
         u32 w[2][16];
         lookup_chunk<BITS>(c[0], tables, w[0]);
-        if constexpr (D < R) c[D] = load_chunk<BITS>(qlane + (size_t)min(r0 + D, g.M - 1) * row_dwords);
+        if constexpr (D < R) c[D] = load_chunk_at<BITS>(row_ptr(D), lane_dword);
 #pragma unroll
         for (int u = 0; u < R; ++u) {
             if (u + 1 < R) {
                 lookup_chunk<BITS>(c[u + 1], tables + (u + 1) * TD, w[(u + 1) & 1]);
-                if (u + 1 + D < R) c[(u + 1 + D) % R] = load_chunk<BITS>(qlane + (size_t)min(r0 + u + 1 + D, g.M - 1) * row_dwords);
+                if (u + 1 + D < R) c[(u + 1 + D) % R] = load_chunk_at<BITS>(row_ptr(u + 1 + D), lane_dword);
             }
             // The look-ups of row u + 1 are issued one at a time between the products of row u (two field extractions,
             // one look-up, the products of one look-up) instead of as a block of 16 -- the workgroups of a launch run in
@@ -587,16 +603,21 @@ __device__ __forceinline__ void matvec_planned_block(const MatvecArgs& g, int bl
             rawv.x = v.x; rawv.y = v.y;
         }
     }
-    const int j0 = wave * kSliceCols + lane * kLaneElems;
-    const bool live = j0 < g.N;
-    const int j0c = live ? j0 : g.N - kLaneElems;
+    const u32 j0 = (u32)wave * kSliceCols + (u32)lane * kLaneElems;
+    const bool live = j0 < (u32)g.N;
+    const u32 j0c = live ? j0 : (u32)g.N - kLaneElems;
     u32 xr[16];
     load_x(x, j0c, xr);
     const size_t row_dwords = (size_t)g.N * BITS / 32;
-    const u32* __restrict__ qlane = static_cast<const u32*>(g.qidx) + (size_t)(j0c / 32) * BITS;
+    const u32 lane_dword = (j0c >> 5) * BITS;                        // the lane's 32 indices inside a row of the index stream
+    const u32* __restrict__ qrow0 = static_cast<const u32*>(g.qidx); // row pointers below are uniform: r0 and M are
+    auto row_ptr = [&](int u) {
+        const u32 row = (u32)__builtin_amdgcn_readfirstlane(min(r0 + u, g.M - 1));   // keeps the 64-bit product on the scalar unit
+        return qrow0 + (size_t)row * row_dwords;
+    };
     LaneChunk<BITS> c[R];
 #pragma unroll
-    for (int u = 0; u < D; ++u) c[u] = load_chunk<BITS>(qlane + (size_t)min(r0 + u, g.M - 1) * row_dwords);
+    for (int u = 0; u < D; ++u) c[u] = load_chunk_at<BITS>(row_ptr(u), lane_dword);
     // The slot batch of this wave in quad q is batch `wave` of that quad's slot; past the slot (wave >= C) the last batch is
     // re-read and ignored.  Entries, tag bytes (one per group, fetched by the group's own lanes) and the overflow descriptors all
     // come through vector loads: a scalar load would have to be waited for together with every LDS operation of the wave.
@@ -629,12 +650,12 @@ __device__ __forceinline__ void matvec_planned_block(const MatvecArgs& g, int bl
     float acc[R];
     u32 w[2][16];
     lookup_chunk<BITS>(c[0], tables, w[0]);
-    if constexpr (D < R) c[D] = load_chunk<BITS>(qlane + (size_t)min(r0 + D, g.M - 1) * row_dwords);
+    if constexpr (D < R) c[D] = load_chunk_at<BITS>(row_ptr(D), lane_dword);
 #pragma unroll
     for (int u = 0; u < R; ++u) {
         if (u + 1 < R) {
             lookup_chunk<BITS>(c[u + 1], tables + (u + 1) * TD, w[(u + 1) & 1]);
-            if (u + 1 + D < R) c[(u + 1 + D) % R] = load_chunk<BITS>(qlane + (size_t)min(r0 + u + 1 + D, g.M - 1) * row_dwords);
+            if (u + 1 + D < R) c[(u + 1 + D) % R] = load_chunk_at<BITS>(row_ptr(u + 1 + D), lane_dword);
         }
         // The activations of the slot batches are gathered once the last row of the index stream has been requested: memory
         // results return in request order, so gathers issued earlier would stand between the wave and its next rows, and a
