@@ -48,6 +48,39 @@ def test_graph_replays_match_the_eager_result(B):
         assert torch.equal(got, want), f"replay {rep}"
 
 
+def test_graph_replays_of_planned_and_multi_layer_calls_match_the_eager_result():
+    """what the decode-step benchmark replays: a planned single-layer call (plan built before the capture) and a multi-layer
+    call, whose descriptors are copied into the kernel arguments at capture time (the host array is dropped before the first
+    replay)"""
+    import torch
+    import paper_2306_07629_amd as sq
+    layers = [gen.make_layer(M, N, 3, frac=0.0045, skew=(0.1, 0.5), seed=60 + k) for k, (M, N) in enumerate([(1030, 4096), (517, 11008), (33, 16384)])]
+    devs = [sq.DeviceLayer(L).build_plan() for L in layers]
+    eager = [D.matvec().clone() for D in devs]
+    torch.cuda.synchronize()
+    for L, y in zip(layers, eager):
+        y_ref, absdot = oracle.layer_matvec(L)
+        assert (np.abs(_f64(y) - y_ref) <= TOL * absdot).all()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            devs[0].matvec()                                                       # planned, one layer
+            desc = sq.layer_descriptors([D.descriptor() for D in devs[1:]])
+            sq.sqllm_dense_sparse_matvec_multi(desc)                               # planned, two layers, eight rows per workgroup
+    del desc
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for D in devs:
+            D.y.fill_(12345)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, (D, y) in enumerate(zip(devs, eager)):
+            assert torch.equal(D.y, y), f"replay {rep}, layer {k}"
+
+
 def test_non_default_stream_and_back_to_back_calls():
     import torch
     import paper_2306_07629_amd as sq
