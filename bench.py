@@ -608,6 +608,12 @@ def main():
                "sample": f"{reps} full passes over the same {len(shapes)} layers (median), fp64, OpenMP over rows",
                "gbs": step_bytes / med / 1e9}
 
+    # ---- context: what a plain device-to-device copy of 1 GiB reaches on this machine (bytes read + bytes written per second)
+    big = [torch.ones(1 << 28, dtype=torch.int32, device="cuda") for _ in range(3)]
+    sec_cp, _ = time_steps(torch, lambda s_: big[2].copy_(big[s_ % 2]), 8, 2, G, 3)
+    copy_gbs = 8 * 2 * (1 << 30) / sec_cp / 1e9
+    del big
+
     out = {
         "metric": f"us per dense+sparse matvec ({bits}-bit LUT + {100 * frac:g}% CSR), effective HBM GB/s in roofline",
         "value": us_per_matvec, "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -623,7 +629,7 @@ def main():
         "warm_us_per_matvec": sec_warm / launches * 1e6, "warm_effective_gbs": step_bytes * args.steps / sec_warm / 1e9,
         "fp16_gemv_us": {"own_kernel": us_f_own, "torch_mv" if B == 1 else "torch_mm": us_f_torch}, "speedup_vs_fp16": us_f / us_per_matvec,
         "parity_worst_err_over_bound": worst, "launch_mode": "hip_graph_replay" if G else "python_ctypes", "host_wall_s_timed_region": wall_cold,
-        "device": device_info(torch),
+        "device": device_info(torch), "context_device_copy_1gib_gbs_read_plus_write": copy_gbs,
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                      "traffic": traffic,
                      "kernel": (f"sqllm::matvec_kernel<{bits},*>" if args.no_plan else f"sqllm::matvec_planned_kernel<{bits},*>") if B == 1 else f"sqllm::matvec_b16_kernel<{bits},*>",
