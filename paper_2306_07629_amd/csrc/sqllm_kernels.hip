@@ -362,6 +362,22 @@ __device__ __forceinline__ void load_row_pointers(const MatvecArgs& g, int r0, i
 
 // The work of one workgroup: rows [R block, R block + R) of layer g, carried by the workgroup's first NW waves
 // (W dense waves, then the sparse wave).
+// Total of one output row over the workgroup's partial sums: `na` values a[i * R + row] followed by `nb` values b[i * R + row].
+// Eight lanes per row (lane = 8 row + p) each add every eighth value in order, then the eight are combined by a butterfly whose
+// every lane forms the same sums; the order depends on the counts only, not on R.  Valid in all eight lanes of a row < R.
+template <int R>
+__device__ __forceinline__ float block_row_total(const float* __restrict__ a, int na, const float* __restrict__ b, int nb, int lane) {
+    const int row = lane >> 3, p = lane & 7;
+    float s = 0.f;
+    if (row < R) {
+        for (int i = p; i < na + nb; i += 8) s += i < na ? a[i * R + row] : b[(i - na) * R + row];
+    }
+    s += dpp_f<kQuadXor1>(0.f, s);
+    s += dpp_f<kQuadXor2>(0.f, s);
+    s += dpp_f<kRowHalfMirror>(0.f, s);
+    return s;
+}
+
 template <int BITS, int R, int D>
 __device__ __forceinline__ void matvec_block(const MatvecArgs& g, int block, int NW) {
     static_assert(D >= 2 && D <= R && (R == 4 || R == 8), "prefetch depth, rows per workgroup");
@@ -497,13 +513,13 @@ __device__ __forceinline__ void matvec_block(const MatvecArgs& g, int block, int
 
     // combine the slice sums and the sparse partial sums in a fixed order, round once
     uint16_t* __restrict__ y = static_cast<uint16_t*>(g.y);
-    if (tid < nrows) {
-        float s = 0.f;
-        for (int w = 0; w < 4 * W; ++w) s += part[w * R + tid];
-        if (sparse)
-            for (int w = 0; w < NW; ++w) s += spart[w * R + tid];
-        if (g.accumulate) s += half_bits_to_float(y[r0 + tid]);
-        y[r0 + tid] = float_to_half_bits(s);
+    if (wave == 0) {
+        float s = block_row_total<R>(part, 4 * W, spart, sparse ? NW : 0, lane);
+        const int row = lane >> 3;
+        if ((lane & 7) == 0 && row < nrows) {
+            if (g.accumulate) s += half_bits_to_float(y[r0 + row]);
+            y[r0 + row] = float_to_half_bits(s);
+        }
     }
 }
 
@@ -728,11 +744,10 @@ __device__ __forceinline__ void matvec_planned_block(const MatvecArgs& g, int bl
     }
     __syncthreads();
     uint16_t* __restrict__ y = static_cast<uint16_t*>(g.y);
-    if (tid < nrows) {
-        float s = 0.f;
-        for (int w2 = 0; w2 < 4 * W; ++w2) s += part[w2 * R + tid];
-        for (int w2 = 0; w2 < W; ++w2) s += spart[w2 * R + tid];
-        y[r0 + tid] = float_to_half_bits(s);
+    if (wave == 0) {
+        const float s = block_row_total<R>(part, 4 * W, spart, W, lane);
+        const int row = lane >> 3;
+        if ((lane & 7) == 0 && row < nrows) y[r0 + row] = float_to_half_bits(s);
     }
 }
 
