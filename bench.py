@@ -169,7 +169,7 @@ DECODE_STEP = {
     # projections that share an input stacked row-wise (q,k,v -> 12288 rows; gate,up -> 22016 rows): 128 launches
     "llama7b_decode_step_3bit_stacked": (32, [(12288, 4096), (4096, 4096), (22016, 4096), (4096, 11008)], 3, 0.0045, (0.10, 0.50)),
     # the same 224 layers through sqllm_dense_sparse_matvec_multi: one call (= one launch) per decoder block, or one call for
-    # the whole step (launches of eight layers).  The matvecs of the synthetic step do not depend on each other.
+    # the whole step (launches of up to 16 layers).  The matvecs of the synthetic step do not depend on each other.
     "llama7b_decode_step_3bit_multi_block": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 3, 0.0045, (0.10, 0.50)),
     "llama7b_decode_step_3bit_multi_step": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 3, 0.0045, (0.10, 0.50)),
 }

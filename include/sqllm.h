@@ -125,7 +125,8 @@ int sqllm_csr_plan_build(int M, int N, long long nnz, const int* rowptr, const i
  *            layout and alignment of the argument of the same name of sqllm_dense_sparse_matvec (B = 1).  All layers of one
  *            call have the same `bits`.  The descriptors are copied into the kernel arguments: the array may be reused or
  *            freed as soon as the call returns.
- * Consecutive layers are merged into launches of up to SQLLM_MAX_LAYERS_PER_LAUNCH layers.  A launch ends early where a layer
+ * Consecutive layers are merged into launches of up to SQLLM_MAX_LAYERS_PER_LAUNCH layers with a plan, or half as many without
+ * (their descriptors are larger, and a launch is fastest while its kernel arguments stay below 1 KiB).  A launch ends early where a layer
  * with a plan follows one without (or the reverse) and, among layers without a plan, where the row width changes between "below
  * 16384" and "16384 and wider" (those two classes run with different rows per workgroup, on which the summation order of their
  * sparse term depends).  Layers with a plan give the same bits whatever the rows per workgroup, so their launches choose it by
@@ -146,7 +147,7 @@ typedef struct {
     const void* x;
     void* y;
 } sqllm_layer;
-#define SQLLM_MAX_LAYERS_PER_LAUNCH 8
+#define SQLLM_MAX_LAYERS_PER_LAUNCH 16
 int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* stream);
 
 /* One thread per row over the CSR matrix — the "standard" kernel the paper's App. C compares the balanced

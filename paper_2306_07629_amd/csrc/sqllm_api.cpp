@@ -200,12 +200,14 @@ int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* 
         const int cls = cls_of(layers[l]);
         long long blocks8 = 0;
         int widest_rule = 4;
-        while (l < count && m.count < sqllm::kMaxLayersPerLaunch && cls_of(layers[l]) == cls) {
+        const int cap = cls == 1 ? sqllm::kMaxLayersPerLaunch : sqllm::kMaxCsrLayersPerLaunch;
+        while (l < count && m.count < cap && cls_of(layers[l]) == cls) {
             const sqllm_layer& L = layers[l];
             if (L.M > 0) {
                 const int k = m.count++;
-                m.M[k] = L.M; m.N[k] = L.N; m.nnz[k] = L.nnz; m.qidx[k] = L.qidx; m.lut[k] = L.lut; m.rowptr[k] = L.rowptr; m.cols[k] = L.cols;
-                m.vals[k] = L.vals; m.x[k] = L.x; m.y[k] = L.y; m.plan[k] = planned_of(L) ? L.plan : nullptr;
+                sqllm::LayerArgs& a = m.layer[k];
+                a.M = L.M; a.N = L.N; a.nnz = L.nnz; a.qidx = L.qidx; a.lut = L.lut; a.rowptr = L.rowptr; a.cols = L.cols;
+                a.vals = L.vals; a.x = L.x; a.y = L.y; a.plan = planned_of(L) ? L.plan : nullptr;
                 blocks8 += (L.M + 7) / 8;
                 if (sqllm::multi_rows_per_workgroup(L.N) == 8) widest_rule = 8;
             }

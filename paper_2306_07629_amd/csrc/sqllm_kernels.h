@@ -38,25 +38,28 @@ struct PlanLayout {
 PlanLayout plan_layout(int M, int N, long long nnz);
 hipError_t launch_plan_build(int M, int N, long long nnz, const int* rowptr, const int* cols, const void* vals, void* plan, hipStream_t s);
 
-// Several independent one-column layers in one launch (passed by value as kernel arguments)
-constexpr int kMaxLayersPerLaunch = 8;
+// Several independent one-column layers in one launch.  The host-side description below is turned by the launcher into the
+// compact argument block the kernel takes by value (only the fields of its class, room for 8 or 16 layers as needed).
+constexpr int kMaxLayersPerLaunch = 16;      // layers with a plan
+constexpr int kMaxCsrLayersPerLaunch = 8;    // layers whose sparse term is read from the CSR arrays (more fields per layer)
+struct LayerArgs {
+    int M, N;
+    long long nnz;
+    const void* qidx;
+    const void* lut;
+    const int* rowptr;
+    const int* cols;
+    const void* vals;
+    const void* x;
+    void* y;
+    const void* plan;       // all layers of a launch have a plan, or none has
+};
 struct MultiArgs {
     int count;
-    int first_block[kMaxLayersPerLaunch + 1];   // filled by the launcher: workgroups of layer l are first_block[l] .. first_block[l + 1] - 1
-    int M[kMaxLayersPerLaunch], N[kMaxLayersPerLaunch];
-    long long nnz[kMaxLayersPerLaunch];
-    const void* qidx[kMaxLayersPerLaunch];
-    const void* lut[kMaxLayersPerLaunch];
-    const int* rowptr[kMaxLayersPerLaunch];
-    const int* cols[kMaxLayersPerLaunch];
-    const void* vals[kMaxLayersPerLaunch];
-    const void* x[kMaxLayersPerLaunch];
-    void* y[kMaxLayersPerLaunch];
-    const void* plan[kMaxLayersPerLaunch];
-    int plan_c[kMaxLayersPerLaunch];            // filled by the launcher
+    LayerArgs layer[kMaxLayersPerLaunch];
 };
 int multi_rows_per_workgroup(int N);             // rows per workgroup of the one-column kernel for rows of N columns (4 or 8)
-hipError_t launch_matvec_multi(MultiArgs& m, int bits, int rows_per_workgroup, hipStream_t s);
+hipError_t launch_matvec_multi(const MultiArgs& m, int bits, int rows_per_workgroup, hipStream_t s);
 
 // Offline side (sqllm_quant.hip): everything is a caller-owned device pointer.
 struct QuantArgs {

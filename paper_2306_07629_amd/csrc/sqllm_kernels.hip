@@ -30,7 +30,7 @@
 //   * With a plan of the sparse term (a one-time re-layout of the CSR arrays, see PlanView) there is no sparse wave: every
 //     dense wave fetches one 64-entry batch of the workgroup's slot at wave start, gathers its activations once its last
 //     index row has been requested, and sums the four 16-entry row groups of the batch with fixed 16-lane reductions.
-//   * matvec_multi_kernel / matvec_planned_multi_kernel run the workgroups of up to eight layers in one grid: a workgroup
+//   * matvec_multi_kernel / matvec_planned_multi_kernel run the workgroups of up to 16 layers in one grid: a workgroup
 //     finds its layer from the first-block table in the kernel arguments and then runs the same per-block code, so every y
 //     is bit for bit that of a launch of its own.
 // Batches: two to sixteen activation columns go to matvec_b16_kernel, which runs the dense and the sparse term on the
@@ -38,6 +38,8 @@
 // lane mapping.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
+#include <type_traits>
 
 #include "sqllm_kernels.h"
 
@@ -756,14 +758,33 @@ __global__ void __launch_bounds__(1024) matvec_planned_kernel(MatvecArgs g) {
     matvec_planned_block<BITS, R, D>(g, blockIdx.x, blockDim.x >> 6);
 }
 
-template <int BITS, int R, int D>
-__global__ void __launch_bounds__(1024) matvec_planned_multi_kernel(MultiArgs m) {
+// The arguments of a multi-layer launch as the kernel takes them (by value): only the fields its class reads, and room for 8 or
+// 16 layers, whichever the launch needs.  The block stays under 1 KiB (16 planned layers: 968 bytes, 8 CSR layers: 616): launches
+// with a larger one were measured 7 to 17 % slower over a whole decode step, whatever the layout of the fields, and a small block
+// is a little faster than a large one below that size too.
+struct PlannedLayer { int M, N, nnz, plan_c; const void *qidx, *lut, *x; void* y; const void* plan; };                            // 56 bytes
+struct CsrLayer { int M, N, nnz, pad; const void *qidx, *lut, *x; void* y; const int* rowptr; const int* cols; const void* vals; };   // 72 bytes
+template <class L, int K>
+struct MultiKernArgs {
+    int count;
+    int first_block[K + 1];
+    L layer[K];
+};
+template <class L, int K>
+__device__ __forceinline__ int layer_of_block(const MultiKernArgs<L, K>& m) {
     int l = 0;
 #pragma unroll
-    for (int k = 1; k < kMaxLayersPerLaunch; ++k) l += (k < m.count && (int)blockIdx.x >= m.first_block[k]) ? 1 : 0;   // uniform
+    for (int k = 1; k < K; ++k) l += (k < m.count && (int)blockIdx.x >= m.first_block[k]) ? 1 : 0;   // uniform
+    return l;
+}
+
+template <int BITS, int R, int D, int K>
+__global__ void __launch_bounds__(1024) matvec_planned_multi_kernel(MultiKernArgs<PlannedLayer, K> m) {
+    const int l = layer_of_block(m);
     MatvecArgs g;
-    g.M = m.M[l]; g.N = m.N[l]; g.bits = BITS; g.B = 1; g.bt0 = 0; g.bn = 1; g.accumulate = 0; g.nnz = m.nnz[l];
-    g.qidx = m.qidx[l]; g.lut = m.lut[l]; g.rowptr = nullptr; g.cols = nullptr; g.vals = nullptr; g.x = m.x[l]; g.y = m.y[l]; g.plan = m.plan[l]; g.plan_c = m.plan_c[l];
+    const PlannedLayer& a = m.layer[l];
+    g.M = a.M; g.N = a.N; g.bits = BITS; g.B = 1; g.bt0 = 0; g.bn = 1; g.accumulate = 0; g.nnz = a.nnz;
+    g.qidx = a.qidx; g.lut = a.lut; g.rowptr = nullptr; g.cols = nullptr; g.vals = nullptr; g.x = a.x; g.y = a.y; g.plan = a.plan; g.plan_c = a.plan_c;
     const int W = (g.N + kSliceCols - 1) / kSliceCols;
     if ((int)(threadIdx.x >> 6) >= W) return;
     matvec_planned_block<BITS, R, D>(g, (int)blockIdx.x - m.first_block[l], W);
@@ -855,14 +876,13 @@ __global__ void __launch_bounds__(1024) matvec_kernel(MatvecArgs g) {
 // workgroup's barriers).  Every layer is computed by the same code, in the same order of operations, as in a launch of its own,
 // so the results are bit for bit those of separate calls -- what is saved is the launch and the ramp between them: the last
 // workgroups of a layer run beside the first of the next.
-template <int BITS, int R, int D>
-__global__ void __launch_bounds__(1024) matvec_multi_kernel(MultiArgs m) {
-    int l = 0;
-#pragma unroll
-    for (int k = 1; k < kMaxLayersPerLaunch; ++k) l += (k < m.count && (int)blockIdx.x >= m.first_block[k]) ? 1 : 0;   // uniform
+template <int BITS, int R, int D, int K>
+__global__ void __launch_bounds__(1024) matvec_multi_kernel(MultiKernArgs<CsrLayer, K> m) {
+    const int l = layer_of_block(m);
     MatvecArgs g;
-    g.M = m.M[l]; g.N = m.N[l]; g.bits = BITS; g.B = 1; g.bt0 = 0; g.bn = 1; g.accumulate = 0; g.nnz = m.nnz[l];
-    g.qidx = m.qidx[l]; g.lut = m.lut[l]; g.rowptr = m.rowptr[l]; g.cols = m.cols[l]; g.vals = m.vals[l]; g.x = m.x[l]; g.y = m.y[l]; g.plan = nullptr;
+    const CsrLayer& a = m.layer[l];
+    g.M = a.M; g.N = a.N; g.bits = BITS; g.B = 1; g.bt0 = 0; g.bn = 1; g.accumulate = 0; g.nnz = a.nnz;
+    g.qidx = a.qidx; g.lut = a.lut; g.rowptr = a.rowptr; g.cols = a.cols; g.vals = a.vals; g.x = a.x; g.y = a.y; g.plan = nullptr;
     const int NW = (g.N + kSliceCols - 1) / kSliceCols + (g.nnz > 0 ? 1 : 0);
     if ((int)(threadIdx.x >> 6) >= NW) return;
     matvec_block<BITS, R, D>(g, (int)blockIdx.x - m.first_block[l], NW);
@@ -1494,32 +1514,48 @@ static hipError_t launch_matvec_planned(const MatvecArgs& g0, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int BITS, int R>
-static hipError_t launch_multi_r(MultiArgs& m, hipStream_t s) {
-    int total = 0, waves = 1;
+template <int BITS, int R, int K, bool PLANNED>
+static hipError_t launch_multi_k(const MultiArgs& m, hipStream_t s) {
+    int total = 0, waves = 1, w2 = 1;
+    typedef typename std::conditional<PLANNED, PlannedLayer, CsrLayer>::type L;
+    MultiKernArgs<L, K> k;
+    memset(&k, 0, sizeof k);
+    k.count = m.count;
     for (int l = 0; l < m.count; ++l) {
-        m.first_block[l] = total;
-        total += (m.M[l] + R - 1) / R;
-        waves = max(waves, (m.N[l] + kSliceCols - 1) / kSliceCols + (m.nnz[l] > 0 ? 1 : 0));
-    }
-    for (int l = m.count; l <= kMaxLayersPerLaunch; ++l) m.first_block[l] = total;
-    if (total == 0) return hipSuccess;
-    if (m.plan[0]) {
-        int w2 = 1;
-        for (int l = 0; l < m.count; ++l) {
-            w2 = max(w2, (m.N[l] + kSliceCols - 1) / kSliceCols);
-            m.plan_c[l] = plan_layout(m.M[l], m.N[l], m.nnz[l]).C;
+        const LayerArgs& a = m.layer[l];
+        k.first_block[l] = total;
+        total += (a.M + R - 1) / R;
+        w2 = max(w2, (a.N + kSliceCols - 1) / kSliceCols);
+        waves = max(waves, (a.N + kSliceCols - 1) / kSliceCols + (a.nnz > 0 ? 1 : 0));
+        L& d = k.layer[l];
+        d.M = a.M; d.N = a.N; d.nnz = (int)a.nnz; d.qidx = a.qidx; d.lut = a.lut; d.x = a.x; d.y = a.y;
+        if constexpr (PLANNED) {
+            d.plan = a.plan;
+            d.plan_c = plan_layout(a.M, a.N, a.nnz).C;
+        } else {
+            d.rowptr = a.rowptr; d.cols = a.cols; d.vals = a.vals;
         }
-        hipLaunchKernelGGL((matvec_planned_multi_kernel<BITS, R, 2>), dim3(total), dim3(w2 * kWave), 0, s, m);
-    } else {
-        hipLaunchKernelGGL((matvec_multi_kernel<BITS, R, 2>), dim3(total), dim3(waves * kWave), 0, s, m);
     }
+    for (int l = m.count; l <= K; ++l) k.first_block[l] = total;
+    if (total == 0) return hipSuccess;
+    if constexpr (PLANNED) hipLaunchKernelGGL((matvec_planned_multi_kernel<BITS, R, 2, K>), dim3(total), dim3(w2 * kWave), 0, s, k);
+    else hipLaunchKernelGGL((matvec_multi_kernel<BITS, R, 2, K>), dim3(total), dim3(waves * kWave), 0, s, k);
     return hipGetLastError();
+}
+template <int BITS, int R>
+static hipError_t launch_multi_r(const MultiArgs& m, hipStream_t s) {
+    if (m.count < 1 || m.count > kMaxLayersPerLaunch) return hipErrorInvalidValue;
+    const bool planned = m.layer[0].plan != nullptr;
+    for (int l = 0; l < m.count; ++l)
+        if ((m.layer[l].plan != nullptr) != planned) return hipErrorInvalidValue;   // one class per launch
+    if (!planned && m.count > kMaxCsrLayersPerLaunch) return hipErrorInvalidValue;
+    if (m.count <= 8) return planned ? launch_multi_k<BITS, R, 8, true>(m, s) : launch_multi_k<BITS, R, 8, false>(m, s);
+    return launch_multi_k<BITS, R, 16, true>(m, s);
 }
 
 int multi_rows_per_workgroup(int N) { return (N + kSliceCols - 1) / kSliceCols >= 8 ? 8 : 4; }
 
-hipError_t launch_matvec_multi(MultiArgs& m, int bits, int R, hipStream_t s) {
+hipError_t launch_matvec_multi(const MultiArgs& m, int bits, int R, hipStream_t s) {
     if (R == 8) return bits == 2 ? launch_multi_r<2, 8>(m, s) : (bits == 3 ? launch_multi_r<3, 8>(m, s) : launch_multi_r<4, 8>(m, s));
     return bits == 2 ? launch_multi_r<2, 4>(m, s) : (bits == 3 ? launch_multi_r<3, 4>(m, s) : launch_multi_r<4, 4>(m, s));
 }

@@ -39,8 +39,8 @@ def test_one_decoder_block_in_one_launch():
 
 @pytest.mark.parametrize("bits", [2, 4])
 def test_more_layers_than_one_launch_holds_and_both_row_classes(bits):
-    """eleven layers: split into launches of eight; a 16384-wide layer in the middle forces a launch boundary of its own (8
-    rows per workgroup); layers without nonzeros and with a single row"""
+    """eleven layers; a 16384-wide layer in the middle forces a launch boundary of its own (8 rows per workgroup); layers without
+    nonzeros and with a single row"""
     specs = [(70, 2048, 0.0045, None), (1, 128, 0.0, None), (300, 2176, 0.01, (0.1, 0.5)), (33, 16384, 0.0045, None), (64, 128, 0.0, None),
              (9, 22016, 0.0045, None), (129, 4096, 0.0005, None), (37, 128, 0.02, None), (200, 1024, 0.0045, (0.01, 0.3)), (5, 8192, 0.0045, None),
              (77, 2304, 0.0045, None)]
@@ -52,3 +52,12 @@ def test_full_size_block_of_the_7b_step():
     specs = [(4096, 4096, 0.0045, (0.1, 0.5))] * 2 + [(11008, 4096, 0.0045, (0.1, 0.5)), (4096, 11008, 0.0045, (0.1, 0.5))]
     print("multi: full-size 7B layers", flush=True)
     run(specs, 3, 7200)
+
+
+def test_more_layers_than_one_launch_holds():
+    """forty small layers: the call splits them into launches of at most SQLLM_MAX_LAYERS_PER_LAUNCH (16)"""
+    rng = np.random.default_rng(77)
+    specs = [(int(rng.integers(1, 40)), int(rng.choice([128, 256, 1024, 2176, 4096])), float(rng.choice([0.0, 0.0045, 0.02])), None) for _ in range(40)]
+    print("multi: forty layers", flush=True)
+    run(specs, 3, 7300)
+

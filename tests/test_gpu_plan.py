@@ -190,8 +190,17 @@ def test_planned_multi_launch_of_many_workgroups_switches_to_eight_rows_and_keep
 
 
 def test_four_full_size_decoder_blocks_in_one_call():
-    """28 full-size layers of a 7B-shaped model (four decoder blocks, a seed per layer) in ONE multi-layer call: launches of eight
-    layers with eight rows per workgroup; every y against the oracle and against the layer's own launch"""
+    """28 full-size layers of a 7B-shaped model (four decoder blocks, a seed per layer) in ONE multi-layer call, eight rows per
+    workgroup; every y against the oracle and against the layer's own launch"""
     block = [(4096, 4096, 0.0045, (0.1, 0.5))] * 4 + [(11008, 4096, 0.0045, (0.1, 0.5))] * 2 + [(4096, 11008, 0.0045, (0.1, 0.5))]
     print("planned multi, four decoder blocks", flush=True)
     planned_multi_equals_separate(block * 4, 3, 9000)
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_forty_small_planned_layers_split_into_launches_of_sixteen(bits):
+    """more planned layers than one launch holds (16): launches of 16, 16 and 8 layers, four rows per workgroup"""
+    rng = np.random.default_rng(91 + bits)
+    specs = [(int(rng.integers(1, 40)), int(rng.choice([128, 256, 1024, 2176, 4096])), float(rng.choice([0.0045, 0.02])), None) for _ in range(40)]
+    print(f"planned multi, forty layers, {bits}-bit", flush=True)
+    planned_multi_equals_separate(specs, bits, 9100 + bits)
