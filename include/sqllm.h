@@ -125,14 +125,16 @@ int sqllm_csr_plan_build(int M, int N, long long nnz, const int* rowptr, const i
  *            layout and alignment of the argument of the same name of sqllm_dense_sparse_matvec (B = 1).  All layers of one
  *            call have the same `bits`.  The descriptors are copied into the kernel arguments: the array may be reused or
  *            freed as soon as the call returns.
- * Consecutive layers are merged into launches of up to SQLLM_MAX_LAYERS_PER_LAUNCH layers with a plan, or half as many without
- * (their descriptors are larger, and a launch is fastest while its kernel arguments stay below 1 KiB).  A launch ends early where a layer
- * with a plan follows one without (or the reverse) and, among layers without a plan, where the row width changes between "below
- * 16384" and "16384 and wider" (those two classes run with different rows per workgroup, on which the summation order of their
- * sparse term depends).  Layers with a plan give the same bits whatever the rows per workgroup, so their launches choose it by
- * size: eight rows when the launch is many generations of workgroups, else what the layers' own launches would take.
+ * The layers of one call must not depend on each other and their y must not overlap; they may run in any order.  The call sorts
+ * them into groups and gives each group launches of its own, of up to SQLLM_MAX_LAYERS_PER_LAUNCH layers with a plan, or half as
+ * many without (their descriptors are larger, and a launch is fastest while its kernel arguments stay below 1 KiB).  A group is the
+ * layers that agree in: plan or no plan; the waves per workgroup they need (one per 2048 columns: every workgroup of a launch has
+ * the size of its widest layer, and starting surplus waves in the narrower ones costs more than a launch); without a plan, the
+ * rows per workgroup of the layer's own launch, on which the summation order of its sparse term depends.  Layers with a plan
+ * give the same bits whatever the rows per workgroup, so their launches choose it by size: eight rows when the launch is many
+ * generations of workgroups, else what the layers' own launches would take.
  * Each y is bit for bit what a separate sqllm_dense_sparse_matvec call with the same arguments gives; what is saved is the launch
- * gap and the ramp-up and tail of every layer but the last, and in long launches part of the fixed work per row.  The layers of one call must not depend on each other and their y must not overlap.
+ * gap and the ramp-up and tail of every layer but the last of a launch, and in long launches part of the fixed work per row.
  * Errors as for sqllm_dense_sparse_matvec, reported for the first offending layer; nothing is enqueued if any layer fails
  * validation.  count == 0 -> SQLLM_OK.                                                                                          */
 typedef struct {

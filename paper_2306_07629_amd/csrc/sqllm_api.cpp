@@ -6,6 +6,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
+#include <vector>
 
 #include "sqllm.h"
 #include "sqllm_kernels.h"
@@ -186,37 +187,50 @@ int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* 
     for (int l = 0; l < count; ++l) any = any || layers[l].M > 0;
     if (!any) return SQLLM_OK;
     if ((st = check_device())) return st;
-    int l = 0;
-    while (l < count) {
-        sqllm::MultiArgs m;
-        memset(&m, 0, sizeof m);
-        // A launch holds layers of one class.  With the sparse term read from the CSR arrays the batches of a workgroup depend on its
-        // rows, so such a layer keeps the rows per workgroup of its single-layer launch (class = that number) and every y stays bit for
-        // bit that of a call of its own.  With a plan y does not depend on the rows per workgroup: all planned layers form one class,
-        // and the launch takes eight rows when it is many generations of workgroups (fewer, longer workgroups amortise their fixed
-        // work; the other layers' workgroups hide their start-up), else what the layers' own launches would take.
-        auto planned_of = [](const sqllm_layer& L) { return L.plan != nullptr && L.nnz > 0; };
-        auto cls_of = [&](const sqllm_layer& L) { return planned_of(L) ? 1 : 2 * sqllm::multi_rows_per_workgroup(L.N); };
-        const int cls = cls_of(layers[l]);
-        long long blocks8 = 0;
-        int widest_rule = 4;
+    // A launch holds layers of one group.  Groups differ in
+    //   * plan or no plan (different kernels);
+    //   * without a plan, the rows per workgroup of the layer's own launch: with the sparse term read from the CSR arrays the
+    //     batches of a workgroup depend on its rows, so such a layer keeps that number and every y stays bit for bit that of a
+    //     call of its own.  With a plan y does not depend on the rows per workgroup, and the launch takes eight rows when it is
+    //     many generations of workgroups (fewer, longer workgroups amortise their fixed work; the other layers' workgroups
+    //     hide their start-up), else what the layers' own launches would take;
+    //   * the waves per workgroup the layer needs (one per 2048 columns): all workgroups of a launch have the size of its widest
+    //     layer and the surplus waves of a narrower layer leave at once, but starting them is not free -- a 7B-shaped step with the
+    //     two-wave and six-wave layers in common launches took 820 us, in launches of their own 630 us.
+    // The layers of a call are independent, so they may run in any order: groups are taken in the order of their first layer.
+    auto planned_of = [](const sqllm_layer& L) { return L.plan != nullptr && L.nnz > 0; };
+    auto key_of = [&](const sqllm_layer& L) {
+        if (L.M <= 0) return -1;
+        const int waves = (L.N + 2047) / 2048 + (L.nnz > 0 && !planned_of(L) ? 1 : 0);   // without a plan one more wave walks the CSR arrays
+        return ((planned_of(L) ? 1 : 2 * sqllm::multi_rows_per_workgroup(L.N)) << 16) | waves;
+    };
+    std::vector<int> key(count);
+    for (int l = 0; l < count; ++l) key[l] = key_of(layers[l]);
+    for (int first = 0; first < count; ++first) {
+        const int kk = key[first];
+        if (kk < 0) continue;
+        const int cls = kk >> 16;
         const int cap = cls == 1 ? sqllm::kMaxLayersPerLaunch : sqllm::kMaxCsrLayersPerLaunch;
-        while (l < count && m.count < cap && cls_of(layers[l]) == cls) {
-            const sqllm_layer& L = layers[l];
-            if (L.M > 0) {
-                const int k = m.count++;
-                sqllm::LayerArgs& a = m.layer[k];
+        int l = first;
+        while (l < count) {
+            sqllm::MultiArgs m;
+            memset(&m, 0, sizeof m);
+            long long blocks8 = 0;
+            for (; l < count && m.count < cap; ++l) {
+                if (key[l] != kk) continue;
+                key[l] = -1;                                        // taken
+                const sqllm_layer& L = layers[l];
+                sqllm::LayerArgs& a = m.layer[m.count++];
                 a.M = L.M; a.N = L.N; a.nnz = L.nnz; a.qidx = L.qidx; a.lut = L.lut; a.rowptr = L.rowptr; a.cols = L.cols;
-                a.vals = L.vals; a.x = L.x; a.y = L.y; a.plan = planned_of(L) ? L.plan : nullptr;
+                a.vals = L.vals; a.x = L.x; a.y = L.y; a.plan = cls == 1 ? L.plan : nullptr;
                 blocks8 += (L.M + 7) / 8;
-                if (sqllm::multi_rows_per_workgroup(L.N) == 8) widest_rule = 8;
             }
-            ++l;
+            if (m.count == 0) break;
+            const int rule = sqllm::multi_rows_per_workgroup(m.layer[0].N);   // the same for every layer of the group
+            const int rows = cls == 1 ? ((blocks8 >= kManyGenerationsBlocks || rule == 8) ? 8 : 4) : cls / 2;
+            const hipError_t e = sqllm::launch_matvec_multi(m, layers[0].bits, rows, static_cast<hipStream_t>(stream));
+            if (e != hipSuccess) return hip_fail(e, "multi-layer matvec launch");
         }
-        if (m.count == 0) continue;
-        const int rows = cls == 1 ? ((blocks8 >= kManyGenerationsBlocks || widest_rule == 8) ? 8 : 4) : cls / 2;
-        const hipError_t e = sqllm::launch_matvec_multi(m, layers[0].bits, rows, static_cast<hipStream_t>(stream));
-        if (e != hipSuccess) return hip_fail(e, "multi-layer matvec launch");
     }
     return SQLLM_OK;
 }
