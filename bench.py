@@ -172,7 +172,10 @@ DECODE_STEP = {
     # the whole step (launches of up to 16 layers).  The matvecs of the synthetic step do not depend on each other.
     "llama7b_decode_step_3bit_multi_block": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 3, 0.0045, (0.10, 0.50)),
     "llama7b_decode_step_3bit_multi_step": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 3, 0.0045, (0.10, 0.50)),
+    # one call per group of projections that are independent in a real decoder block too: (q, k, v), (o), (gate, up), (down)
+    "llama7b_decode_step_3bit_multi_groups": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 3, 0.0045, (0.10, 0.50)),
 }
+MULTI_GROUPS = [3, 1, 2, 1]
 
 
 def bench_decode_step(args, emit=True, fp16=True):
@@ -209,10 +212,14 @@ def bench_decode_step(args, emit=True, fp16=True):
     torch.cuda.synchronize()
     n_layers = len(dev)
 
-    multi = "multi_block" if args.workload.endswith("_multi_block") else ("multi_step" if args.workload.endswith("_multi_step") else None)
+    multi = next((m for m in ("multi_block", "multi_step", "multi_groups") if args.workload.endswith("_" + m)), None)
     if multi:
-        per_call = len(shapes) if multi == "multi_block" else n_layers
-        calls = [sq.layer_descriptors([D.descriptor() for D in dev[i:i + per_call]]) for i in range(0, n_layers, per_call)]
+        sizes = {"multi_block": [len(shapes)], "multi_step": [n_layers], "multi_groups": MULTI_GROUPS}[multi]
+        calls, i = [], 0
+        while i < n_layers:
+            for n in sizes:
+                calls.append(sq.layer_descriptors([D.descriptor() for D in dev[i:i + n]]))
+                i += n
         # the multi-layer call must reproduce the bits of the single-layer entry point (itself checked against the oracle above)
         for D in dev:
             D.matvec()
@@ -280,7 +287,7 @@ def bench_decode_step(args, emit=True, fp16=True):
         "config": {"workload": args.workload, "blocks": blocks, "layers_per_block": [f"{M}x{N}" for M, N in shapes], "bits": bits, "sparse_frac": frac,
                    "skew": skew, "batch": 1, "seed": SEED, "distinct_layers_resident": n_layers, "resident_gb": step_bytes / 1e9,
                    "parity_checked_blocks": checked, "matvecs_per_step": n_layers, "sparse_term": "CSR arrays" if args.no_plan else "plan built once per matrix",
-                   "entry_point": "sqllm_dense_sparse_matvec_multi, one call per " + ("decoder block" if multi == "multi_block" else "step") if multi else "sqllm_dense_sparse_matvec, one call per layer"},
+                   "entry_point": "sqllm_dense_sparse_matvec_multi, one call per " + {"multi_block": "decoder block", "multi_step": "step", "multi_groups": "group of independent projections (q,k,v | o | gate,up | down)"}[multi] if multi else "sqllm_dense_sparse_matvec, one call per layer"},
         "replay_stats_ms_for_K_steps": REPLAY_STATS.get("cold"),
         "us_per_matvec": us_step / n_layers, "effective_gbs": gbs, "pct_of_hbm_roofline": 100.0 * gbs / HBM_PEAK_GBS,
         "fp16_step_us": {"own_kernel": us_own, "torch_mv": us_torch}, "speedup_vs_fp16": min(us_own, us_torch) / us_step if fp16 else None,

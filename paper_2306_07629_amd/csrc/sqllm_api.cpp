@@ -226,6 +226,13 @@ int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* 
                 blocks8 += (L.M + 7) / 8;
             }
             if (m.count == 0) break;
+            if (m.count == 1) {
+                // a launch of one layer is that layer's own launch: the single-layer kernel starts a little earlier (it does
+                // not have to find its layer in the kernel arguments first)
+                const sqllm::LayerArgs& a = m.layer[0];
+                if ((st = run_matvec(a.M, a.N, layers[0].bits, a.nnz, 1, a.qidx, a.lut, a.rowptr, a.cols, a.vals, a.plan, a.x, a.y, 0, stream))) return st;
+                continue;
+            }
             const int rule = sqllm::multi_rows_per_workgroup(m.layer[0].N);   // the same for every layer of the group
             const int rows = cls == 1 ? ((blocks8 >= kManyGenerationsBlocks || rule == 8) ? 8 : 4) : cls / 2;
             const hipError_t e = sqllm::launch_matvec_multi(m, layers[0].bits, rows, static_cast<hipStream_t>(stream));
