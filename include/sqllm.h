@@ -136,7 +136,7 @@ int sqllm_csr_plan_build(int M, int N, long long nnz, const int* rowptr, const i
  * Each y is bit for bit what a separate sqllm_dense_sparse_matvec call with the same arguments gives; what is saved is the launch
  * gap and the ramp-up and tail of every layer but the last of a launch, and in long launches part of the fixed work per row.
  * Errors as for sqllm_dense_sparse_matvec, reported for the first offending layer; nothing is enqueued if any layer fails
- * validation.  count == 0 -> SQLLM_OK.                                                                                          */
+ * validation (more than 256 layers need a host allocation for the launch order: SQLLM_ERR_SHAPE if it fails).  count == 0 -> SQLLM_OK.                                                                                          */
 typedef struct {
     int M, N, bits;
     long long nnz;

@@ -204,7 +204,17 @@ int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* 
         const int waves = (L.N + 2047) / 2048 + (L.nnz > 0 && !planned_of(L) ? 1 : 0);   // without a plan one more wave walks the CSR arrays
         return ((planned_of(L) ? 1 : 2 * sqllm::multi_rows_per_workgroup(L.N)) << 16) | waves;
     };
-    std::vector<int> key(count);
+    int key_few[256];                                               // a decode step of a 7B-shaped model is 224 layers: no allocation for it
+    std::vector<int> key_many;
+    int* key = key_few;
+    if (count > 256) {
+        try {
+            key_many.resize(count);
+        } catch (...) {
+            return fail(SQLLM_ERR_SHAPE, "count = %d: out of host memory for the launch order", count);
+        }
+        key = key_many.data();
+    }
     for (int l = 0; l < count; ++l) key[l] = key_of(layers[l]);
     for (int first = 0; first < count; ++first) {
         const int kk = key[first];

@@ -204,3 +204,36 @@ def test_forty_small_planned_layers_split_into_launches_of_sixteen(bits):
     specs = [(int(rng.integers(1, 40)), int(rng.choice([128, 256, 1024, 2176, 4096])), float(rng.choice([0.0045, 0.02])), None) for _ in range(40)]
     print(f"planned multi, forty layers, {bits}-bit", flush=True)
     planned_multi_equals_separate(specs, bits, 9100 + bits)
+
+
+def test_three_hundred_mixed_layers_in_one_call_are_regrouped_and_keep_the_bits():
+    """300 small layers in one call, with and without a plan, widths of 1 to 11 waves in shuffled order: the call sorts them into
+    groups (plan or none, waves per workgroup, row class) and launches group by group; every y must be that of the layer's own
+    call, and rows the call does not own stay untouched"""
+    import torch
+    import paper_2306_07629_amd as sq
+    rng = np.random.default_rng(4242)
+    widths = [128, 2048, 2176, 4096, 6144, 8192, 11008, 16384, 22016]
+    layers, devs = [], []
+    for k in range(300):
+        M, N = int(rng.integers(1, 20)), int(rng.choice(widths))
+        frac = float(rng.choice([0.0, 0.0045, 0.03]))
+        L = gen.make_layer(M, N, 3, frac=frac, skew=None, seed=9300 + k)
+        D = sq.DeviceLayer(L)
+        if rng.integers(0, 2) and L.nnz > 0:
+            D.build_plan()
+        layers.append(L)
+        devs.append(D)
+    print("mixed multi, 300 layers", flush=True)
+    sep = []
+    for D in devs:
+        sep.append(D.matvec().clone())
+        D.y.fill_(0x7BFF)
+    torch.cuda.synchronize()
+    sq.sqllm_dense_sparse_matvec_multi([D.descriptor() for D in devs])
+    torch.cuda.synchronize()
+    for k, (L, D, y1) in enumerate(zip(layers, devs, sep)):
+        assert torch.equal(D.y, y1), f"layer {k} ({L.M}x{L.N}, nnz {L.nnz}) differs from the separate call"
+    y_ref, absdot = oracle.layer_matvec(layers[7])
+    err = np.abs(devs[7].y.cpu().numpy().view(np.float16).astype(np.float64) - y_ref)
+    assert (err <= TOL * absdot + 2.0 ** -25).all()
