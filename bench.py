@@ -168,8 +168,9 @@ DECODE_STEP = {
     "llama7b_decode_step_4bit": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 4, 0.0045, (0.10, 0.50)),
     # projections that share an input stacked row-wise (q,k,v -> 12288 rows; gate,up -> 22016 rows): 128 launches
     "llama7b_decode_step_3bit_stacked": (32, [(12288, 4096), (4096, 4096), (22016, 4096), (4096, 11008)], 3, 0.0045, (0.10, 0.50)),
-    # the same 224 layers through sqllm_dense_sparse_matvec_multi: one call (= one launch) per decoder block, or one call for
-    # the whole step (launches of up to 16 layers).  The matvecs of the synthetic step do not depend on each other.
+    # the same 224 layers through sqllm_dense_sparse_matvec_multi: one call per decoder block (two launches: the six 4096-wide
+    # layers, the 11008-wide one), or one call for the whole step (14 launches of 16 layers).  The matvecs of the synthetic step
+    # do not depend on each other.
     "llama7b_decode_step_3bit_multi_block": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 3, 0.0045, (0.10, 0.50)),
     "llama7b_decode_step_3bit_multi_step": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 3, 0.0045, (0.10, 0.50)),
     # one call per group of projections that are independent in a real decoder block too: (q, k, v), (o), (gate, up), (down)
