@@ -152,6 +152,15 @@ typedef struct {
 #define SQLLM_MAX_LAYERS_PER_LAUNCH 16
 int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* stream);
 
+/* The launches sqllm_dense_sparse_matvec_multi would make for these layers, for inspection and tests (host only: no GPU is
+ * needed, nothing is enqueued, no pointer inside a descriptor is followed).
+ *   launch_out    HOST int[count]: the number (0, 1, ...) of the launch layer l goes to, in the order the launches are enqueued;
+ *                 -1 for a layer without rows
+ *   rows_out      HOST int[count] or NULL: rows per workgroup of that launch (4 or 8; 0 for a layer without rows)
+ *   launches_out  HOST int or NULL: number of launches
+ * Validation and errors as for sqllm_dense_sparse_matvec_multi (SQLLM_ERR_NULL also for launch_out == NULL with count > 0).     */
+int sqllm_multi_launch_order(int count, const sqllm_layer* layers, int* launch_out, int* rows_out, int* launches_out);
+
 /* One thread per row over the CSR matrix — the "standard" kernel the paper's App. C compares the balanced
  * one against.  Same arguments and result as sqllm_csr_spmv; kept as the ablation baseline.              */
 int sqllm_csr_spmv_rowwise(int M, int N, long long nnz, int B,

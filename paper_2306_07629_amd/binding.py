@@ -14,7 +14,7 @@ OK = 0
 STATUS_NAMES = ["SQLLM_OK", "SQLLM_ERR_NULL", "SQLLM_ERR_BITS", "SQLLM_ERR_SHAPE", "SQLLM_ERR_ALIGN", "SQLLM_ERR_NNZ",
                 "SQLLM_ERR_BATCH", "SQLLM_ERR_HIP", "SQLLM_ERR_DEVICE"]
 
-EXPORTS = ["sqllm_lut_gemv", "sqllm_csr_spmv", "sqllm_dense_sparse_matvec", "sqllm_dense_sparse_matvec_multi", "sqllm_csr_spmv_rowwise",
+EXPORTS = ["sqllm_lut_gemv", "sqllm_csr_spmv", "sqllm_dense_sparse_matvec", "sqllm_dense_sparse_matvec_multi", "sqllm_multi_launch_order", "sqllm_csr_spmv_rowwise",
            "sqllm_csr_plan_bytes", "sqllm_csr_plan_build",
            "sqllm_unpack_indices", "sqllm_dequantize", "sqllm_fp16_gemv", "sqllm_algorithmic_bytes",
            "sqllm_quantize_workspace_bytes", "sqllm_quantize_layer", "sqllm_quantize_layer_noalloc", "sqllm_extraction_counts",
@@ -50,6 +50,7 @@ def lib() -> ctypes.CDLL:
         L.sqllm_csr_plan_bytes.argtypes = [i32, i32, i64, ctypes.POINTER(ctypes.c_size_t)]
         L.sqllm_csr_plan_build.argtypes = [i32, i32, i64, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.sqllm_dense_sparse_matvec_multi.argtypes = [i32, ctypes.POINTER(LayerDesc), vp]
+        L.sqllm_multi_launch_order.argtypes = [i32, ctypes.POINTER(LayerDesc), ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.sqllm_unpack_indices.argtypes = [i32, i32, i32, vp, vp, vp]
         L.sqllm_dequantize.argtypes = [i32, i32, i32, vp, vp, vp, vp]
         L.sqllm_fp16_gemv.argtypes = [i32, i32, i32, vp, vp, vp, vp]
@@ -139,6 +140,15 @@ def sqllm_dense_sparse_matvec_multi(layers, stream=None):
     """layers: a ctypes array from layer_descriptors(), or the list of tuples it takes"""
     arr = layers if isinstance(layers, ctypes.Array) else layer_descriptors(layers)
     _check(lib().sqllm_dense_sparse_matvec_multi(len(arr), arr, _stream(stream)))
+
+
+def sqllm_multi_launch_order(layers):
+    """(launch number per layer, rows per workgroup per layer, number of launches) of sqllm_dense_sparse_matvec_multi(layers)"""
+    arr = layers if isinstance(layers, ctypes.Array) else layer_descriptors(layers)
+    n = len(arr)
+    launch, rows, total = (ctypes.c_int * max(n, 1))(), (ctypes.c_int * max(n, 1))(), ctypes.c_int(0)
+    _check(lib().sqllm_multi_launch_order(n, arr, launch, rows, ctypes.byref(total)))
+    return list(launch[:n]), list(rows[:n]), total.value
 
 
 def sqllm_unpack_indices(M, N, bits, qidx, idx_out, stream=None):

@@ -166,8 +166,11 @@ int sqllm_csr_plan_build(int M, int N, long long nnz, const int* rowptr, const i
 // workgroups of eight rows from which a planned multi-layer launch counts as many generations (256 compute units hold about 1800)
 static const long long kManyGenerationsBlocks = 4096;
 
-int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* stream) {
-    static_assert(SQLLM_MAX_LAYERS_PER_LAUNCH == sqllm::kMaxLayersPerLaunch, "header and kernels disagree");
+}  // extern "C"
+
+namespace {
+
+int validate_layers(int count, const sqllm_layer* layers) {
     if (count < 0) return fail(SQLLM_ERR_SHAPE, "count = %d is negative", count);
     if (count == 0) return SQLLM_OK;
     if (!layers) return fail(SQLLM_ERR_NULL, "layers must not be NULL");
@@ -183,21 +186,24 @@ int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* 
         }
         if (L.bits != layers[0].bits) return fail(SQLLM_ERR_BITS, "layer %d: bits = %d, layer 0 has %d (one width per call)", l, L.bits, layers[0].bits);
     }
-    bool any = false;
-    for (int l = 0; l < count; ++l) any = any || layers[l].M > 0;
-    if (!any) return SQLLM_OK;
-    if ((st = check_device())) return st;
-    // A launch holds layers of one group.  Groups differ in
-    //   * plan or no plan (different kernels);
-    //   * without a plan, the rows per workgroup of the layer's own launch: with the sparse term read from the CSR arrays the
-    //     batches of a workgroup depend on its rows, so such a layer keeps that number and every y stays bit for bit that of a
-    //     call of its own.  With a plan y does not depend on the rows per workgroup, and the launch takes eight rows when it is
-    //     many generations of workgroups (fewer, longer workgroups amortise their fixed work; the other layers' workgroups
-    //     hide their start-up), else what the layers' own launches would take;
-    //   * the waves per workgroup the layer needs (one per 2048 columns): all workgroups of a launch have the size of its widest
-    //     layer and the surplus waves of a narrower layer leave at once, but starting them is not free -- a 7B-shaped step with the
-    //     two-wave and six-wave layers in common launches took 820 us, in launches of their own 630 us.
-    // The layers of a call are independent, so they may run in any order: groups are taken in the order of their first layer.
+    return SQLLM_OK;
+}
+
+// Sorts the layers of a call into launches and hands each to fn(indices of its layers, their number, planned, rows per workgroup).
+// A launch holds layers of one group.  Groups differ in
+//   * plan or no plan (different kernels);
+//   * without a plan, the rows per workgroup of the layer's own launch: with the sparse term read from the CSR arrays the
+//     batches of a workgroup depend on its rows, so such a layer keeps that number and every y stays bit for bit that of a
+//     call of its own.  With a plan y does not depend on the rows per workgroup, and the launch takes eight rows when it is
+//     many generations of workgroups (fewer, longer workgroups amortise their fixed work; the other layers' workgroups
+//     hide their start-up), else what the layers' own launches would take;
+//   * the waves per workgroup the layer needs (one per 2048 columns): all workgroups of a launch have the size of its widest
+//     layer and the surplus waves of a narrower layer leave at once, but starting them is not free -- a 7B-shaped step with the
+//     two-wave and six-wave layers in common launches took 820 us, in launches of their own 630 us.
+// The layers of a call are independent, so they may run in any order: groups are taken in the order of their first layer.
+// Layers without rows belong to no launch.
+template <class Fn>
+int for_each_launch(int count, const sqllm_layer* layers, Fn&& fn) {
     auto planned_of = [](const sqllm_layer& L) { return L.plan != nullptr && L.nnz > 0; };
     auto key_of = [&](const sqllm_layer& L) {
         if (L.M <= 0) return -1;
@@ -220,35 +226,82 @@ int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* 
         const int kk = key[first];
         if (kk < 0) continue;
         const int cls = kk >> 16;
-        const int cap = cls == 1 ? sqllm::kMaxLayersPerLaunch : sqllm::kMaxCsrLayersPerLaunch;
+        const bool planned = cls == 1;
+        const int cap = planned ? sqllm::kMaxLayersPerLaunch : sqllm::kMaxCsrLayersPerLaunch;
+        const int rule = sqllm::multi_rows_per_workgroup(layers[first].N);   // the same for every layer of the group
         int l = first;
         while (l < count) {
-            sqllm::MultiArgs m;
-            memset(&m, 0, sizeof m);
+            int idx[sqllm::kMaxLayersPerLaunch], n = 0;
             long long blocks8 = 0;
-            for (; l < count && m.count < cap; ++l) {
+            for (; l < count && n < cap; ++l) {
                 if (key[l] != kk) continue;
                 key[l] = -1;                                        // taken
-                const sqllm_layer& L = layers[l];
-                sqllm::LayerArgs& a = m.layer[m.count++];
-                a.M = L.M; a.N = L.N; a.nnz = L.nnz; a.qidx = L.qidx; a.lut = L.lut; a.rowptr = L.rowptr; a.cols = L.cols;
-                a.vals = L.vals; a.x = L.x; a.y = L.y; a.plan = cls == 1 ? L.plan : nullptr;
-                blocks8 += (L.M + 7) / 8;
+                idx[n++] = l;
+                blocks8 += (layers[l].M + 7) / 8;
             }
-            if (m.count == 0) break;
-            if (m.count == 1) {
-                // a launch of one layer is that layer's own launch: the single-layer kernel starts a little earlier (it does
-                // not have to find its layer in the kernel arguments first)
-                const sqllm::LayerArgs& a = m.layer[0];
-                if ((st = run_matvec(a.M, a.N, layers[0].bits, a.nnz, 1, a.qidx, a.lut, a.rowptr, a.cols, a.vals, a.plan, a.x, a.y, 0, stream))) return st;
-                continue;
-            }
-            const int rule = sqllm::multi_rows_per_workgroup(m.layer[0].N);   // the same for every layer of the group
-            const int rows = cls == 1 ? ((blocks8 >= kManyGenerationsBlocks || rule == 8) ? 8 : 4) : cls / 2;
-            const hipError_t e = sqllm::launch_matvec_multi(m, layers[0].bits, rows, static_cast<hipStream_t>(stream));
-            if (e != hipSuccess) return hip_fail(e, "multi-layer matvec launch");
+            if (n == 0) break;
+            // a launch of one layer is that layer's own launch, with its own rule
+            const int rows = planned ? ((rule == 8 || (n > 1 && blocks8 >= kManyGenerationsBlocks)) ? 8 : 4) : cls / 2;
+            const int st = fn(idx, n, planned, rows);
+            if (st) return st;
         }
     }
+    return SQLLM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sqllm_dense_sparse_matvec_multi(int count, const sqllm_layer* layers, void* stream) {
+    static_assert(SQLLM_MAX_LAYERS_PER_LAUNCH == sqllm::kMaxLayersPerLaunch, "header and kernels disagree");
+    int st;
+    if ((st = validate_layers(count, layers))) return st;
+    bool any = false;
+    for (int l = 0; l < count; ++l) any = any || layers[l].M > 0;
+    if (!any) return SQLLM_OK;
+    if ((st = check_device())) return st;
+    return for_each_launch(count, layers, [&](const int* idx, int n, bool planned, int rows) -> int {
+        if (n == 1) {
+            // the single-layer kernel starts a little earlier: it does not have to find its layer in the kernel arguments first
+            const sqllm_layer& L = layers[idx[0]];
+            return run_matvec(L.M, L.N, L.bits, L.nnz, 1, L.qidx, L.lut, L.rowptr, L.cols, L.vals, planned ? L.plan : nullptr, L.x, L.y, 0, stream);
+        }
+        sqllm::MultiArgs m;
+        memset(&m, 0, sizeof m);
+        m.count = n;
+        for (int k = 0; k < n; ++k) {
+            const sqllm_layer& L = layers[idx[k]];
+            sqllm::LayerArgs& a = m.layer[k];
+            a.M = L.M; a.N = L.N; a.nnz = L.nnz; a.qidx = L.qidx; a.lut = L.lut; a.rowptr = L.rowptr; a.cols = L.cols;
+            a.vals = L.vals; a.x = L.x; a.y = L.y; a.plan = planned ? L.plan : nullptr;
+        }
+        const hipError_t e = sqllm::launch_matvec_multi(m, layers[0].bits, rows, static_cast<hipStream_t>(stream));
+        return e != hipSuccess ? hip_fail(e, "multi-layer matvec launch") : SQLLM_OK;
+    });
+}
+
+int sqllm_multi_launch_order(int count, const sqllm_layer* layers, int* launch_out, int* rows_out, int* launches_out) {
+    int st;
+    if ((st = validate_layers(count, layers))) return st;
+    if (count > 0 && !launch_out) return fail(SQLLM_ERR_NULL, "launch_out must not be NULL");
+    for (int l = 0; l < count; ++l) {
+        launch_out[l] = -1;
+        if (rows_out) rows_out[l] = 0;
+    }
+    int launches = 0;
+    if (count > 0) {
+        st = for_each_launch(count, layers, [&](const int* idx, int n, bool, int rows) -> int {
+            for (int k = 0; k < n; ++k) {
+                launch_out[idx[k]] = launches;
+                if (rows_out) rows_out[idx[k]] = rows;
+            }
+            ++launches;
+            return SQLLM_OK;
+        });
+        if (st) return st;
+    }
+    if (launches_out) *launches_out = launches;
     return SQLLM_OK;
 }
 
