@@ -179,6 +179,17 @@ DECODE_STEP = {
 MULTI_GROUPS = [3, 1, 2, 1]
 
 
+def committed_traffic(workload, no_plan):
+    """HBM bytes per matvec from the rocprofv3 counter summary committed for this workload, or None"""
+    tpath = os.path.join(ROOT, "profiles", "traffic_" + workload + ".json")
+    if not os.path.exists(tpath):
+        return None
+    try:
+        return json.load(open(tpath)).get("hbm_bytes_per_launch_no_plan" if no_plan else "hbm_bytes_per_launch")
+    except Exception:
+        return None
+
+
 def bench_decode_step(args, emit=True, fp16=True):
     import numpy as np
     import torch
@@ -293,7 +304,8 @@ def bench_decode_step(args, emit=True, fp16=True):
         "us_per_matvec": us_step / n_layers, "effective_gbs": gbs, "pct_of_hbm_roofline": 100.0 * gbs / HBM_PEAK_GBS,
         "fp16_step_us": {"own_kernel": us_own, "torch_mv": us_torch}, "speedup_vs_fp16": min(us_own, us_torch) / us_step if fp16 else None,
         "parity_worst_err_over_bound": worst, "launch_mode": "hip_graph_replay" if G else "python_ctypes", "host_wall_s_timed_region": wall,
-        "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                     "traffic": committed_traffic(args.workload, args.no_plan),      # per matvec, like algorithmic_bytes_per_launch
                      "kernel": f"sqllm::matvec{'_planned' if not args.no_plan else ''}{'_multi' if multi else ''}_kernel<{bits},*>",
                      "algorithmic_bytes_per_launch": step_bytes / n_layers},
         "cpu_baseline": cpu,
@@ -591,13 +603,7 @@ def main():
     del wring
 
     # ---- HBM traffic per launch measured with rocprofv3 counters, if a summary is committed
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic_" + args.workload + ".json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch_no_plan" if args.no_plan else "hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+    traffic = committed_traffic(args.workload, args.no_plan)
 
     # ---- CPU baseline: the oracle as it stands, on this machine's host cores, bounded sample
     cpu = None
