@@ -175,6 +175,7 @@ DECODE_STEP = {
     "llama7b_decode_step_3bit_multi_step": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 3, 0.0045, (0.10, 0.50)),
     # one call per group of projections that are independent in a real decoder block too: (q, k, v), (o), (gate, up), (down)
     "llama7b_decode_step_3bit_multi_groups": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 3, 0.0045, (0.10, 0.50)),
+    "llama7b_decode_step_4bit_multi_step": (32, [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)], 4, 0.0045, (0.10, 0.50)),
 }
 MULTI_GROUPS = [3, 1, 2, 1]
 
