@@ -140,6 +140,31 @@ __device__ __forceinline__ void pair_offsets(const LaneChunk<2>& c, u32 (&a)[16]
     for (int p = 0; p < 16; ++p) a[p] = ((c.q[p >> 3] >> (4 * (p & 7))) & 0xF) << 2;
 }
 
+// the offset of pair p alone (p a compile-time constant after unrolling): the same values as pair_offsets
+__device__ __forceinline__ u32 pair_offset_of(const LaneChunk<3>& c, int p) {
+    const u32 q0 = c.q[0], q1 = c.q[1], q2 = c.q[2];
+    switch (p) {
+        case 0: return (q0 << 2) & 0xFC;
+        case 1: return (q0 >> 4) & 0xFC;
+        case 2: return (q0 >> 10) & 0xFC;
+        case 3: return (q0 >> 16) & 0xFC;
+        case 4: return (q0 >> 22) & 0xFC;
+        case 5: return funnel_shr(q1, q0, 28) & 0xFC;
+        case 6: return (q1 >> 2) & 0xFC;
+        case 7: return (q1 >> 8) & 0xFC;
+        case 8: return (q1 >> 14) & 0xFC;
+        case 9: return (q1 >> 20) & 0xFC;
+        case 10: return funnel_shr(q2, q1, 26) & 0xFC;
+        case 11: return q2 & 0xFC;
+        case 12: return (q2 >> 6) & 0xFC;
+        case 13: return (q2 >> 12) & 0xFC;
+        case 14: return (q2 >> 18) & 0xFC;
+        default: return (q2 >> 24) & 0xFC;
+    }
+}
+__device__ __forceinline__ u32 pair_offset_of(const LaneChunk<4>& c, int p) { return ((c.q[p >> 2] >> (8 * (p & 3))) & 0xFF) << 2; }
+__device__ __forceinline__ u32 pair_offset_of(const LaneChunk<2>& c, int p) { return ((c.q[p >> 3] >> (4 * (p & 7))) & 0xF) << 2; }
+
 template <int BITS>
 struct TableShape {
     static constexpr int kEntryBits = 2 * BITS;               // a table entry holds the pair of two neighbouring indices: 4, 6 or 8 bits
@@ -456,26 +481,31 @@ __device__ __forceinline__ void matvec_block(const MatvecArgs& g, int block, int
         // software pipeline: the look-ups of row u + 1 are in flight while the products of row u are formed;
         // row u + D of the index stream is requested when row u has been handed to the look-ups
         float acc[R];
-        u32 w[2][16];
-        lookup_chunk<BITS>(c[0], tables, w[0]);
+        u32 w[16];
+        lookup_chunk<BITS>(c[0], tables, w);
         if constexpr (D < R) c[D] = load_chunk_at<BITS>(row_ptr(D), lane_dword);
 #pragma unroll
         for (int u = 0; u < R; ++u) {
-            if (u + 1 < R) {
-                lookup_chunk<BITS>(c[u + 1], tables + (u + 1) * TD, w[(u + 1) & 1]);
-                if (u + 1 + D < R) c[(u + 1 + D) % R] = load_chunk_at<BITS>(row_ptr(u + 1 + D), lane_dword);
-            }
-            // The look-ups of row u + 1 are issued one at a time between the products of row u (two field extractions,
-            // one look-up, the products of one look-up) instead of as a block of 16 -- the workgroups of a launch run in
-            // step, and blocks of look-ups from all of them fill the LDS queue while the vector ALUs idle.
-            acc[u] = dot_chunk(w[u & 1], xr);
-            if (u + 1 < R) {
+            if (u + 1 + D < R) c[(u + 1 + D) % R] = load_chunk_at<BITS>(row_ptr(u + 1 + D), lane_dword);
+            // The look-ups of row u + 1 are issued one at a time between the products of row u (the product of a pair, two field
+            // extractions, one look-up) instead of as a block of 16 -- the workgroups of a launch run in step, and blocks of
+            // look-ups from all of them fill the LDS queue while the vector ALUs idle.
+            // One set of 16 registers holds the pairs of both rows: the look-up of pair p of row u + 1 goes into the register the
+            // product of pair p of row u has just read (two sets cost 8 to 16 registers per lane, i.e. a wave per SIMD).  The products
+            // run in the two accumulator chains of dot_chunk; the scheduling barrier after every step keeps the order.
+            {
+                float a0 = 0.f, a1 = 0.f;
+                const char* tb = reinterpret_cast<const char*>(tables + (u + 1 < R ? u + 1 : 0) * TD);
 #pragma unroll
                 for (int p = 0; p < 16; ++p) {
-                    __builtin_amdgcn_sched_group_barrier(0x2, 2, 0);          // VALU: the offsets of one look-up
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        // DS read
-                    __builtin_amdgcn_sched_group_barrier(0x2, 1, 0);          // VALU: the products of one look-up
+                    if (p & 1) a1 = __builtin_amdgcn_fdot2(as_half2(w[p]), as_half2(xr[p]), a1, false);
+                    else a0 = __builtin_amdgcn_fdot2(as_half2(w[p]), as_half2(xr[p]), a0, false);
+                    if (u + 1 < R) {
+                        w[p] = *reinterpret_cast<const u32*>(tb + pair_offset_of(c[u + 1], p));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
+                acc[u] = a0 + a1;
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -666,13 +696,12 @@ __device__ __forceinline__ void matvec_planned_block(const MatvecArgs& g, int bl
     }
     __syncthreads();
     float acc[R];
-    u32 w[2][16];
-    lookup_chunk<BITS>(c[0], tables, w[0]);
+    u32 w[16];                                                       // the pairs of the current row; each is replaced by the next row's once its product is formed
+    lookup_chunk<BITS>(c[0], tables, w);
     if constexpr (D < R) c[D] = load_chunk_at<BITS>(row_ptr(D), lane_dword);
 #pragma unroll
     for (int u = 0; u < R; ++u) {
         if (u + 1 < R) {
-            lookup_chunk<BITS>(c[u + 1], tables + (u + 1) * TD, w[(u + 1) & 1]);
             if (u + 1 + D < R) c[(u + 1 + D) % R] = load_chunk_at<BITS>(row_ptr(u + 1 + D), lane_dword);
         }
         // The activations of the slot batches are gathered once the last row of the index stream has been requested: memory
@@ -697,14 +726,21 @@ __device__ __forceinline__ void matvec_planned_block(const MatvecArgs& g, int bl
                 }
             }
         }
-        acc[u] = dot_chunk(w[u & 1], xr);
-        if (u + 1 < R) {
+        // products of row u in the two accumulator chains of dot_chunk; the look-ups of row u + 1 take over its registers one by one
+        // (as in matvec_block)
+        {
+            float a0 = 0.f, a1 = 0.f;
+            const char* tb = reinterpret_cast<const char*>(tables + (u + 1 < R ? u + 1 : 0) * TD);
 #pragma unroll
             for (int p = 0; p < 16; ++p) {
-                __builtin_amdgcn_sched_group_barrier(0x2, 2, 0);              // VALU: the offsets of one look-up
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);            // DS read
-                __builtin_amdgcn_sched_group_barrier(0x2, 1, 0);              // VALU: the products of one look-up
+                if (p & 1) a1 = __builtin_amdgcn_fdot2(as_half2(w[p]), as_half2(xr[p]), a1, false);
+                else a0 = __builtin_amdgcn_fdot2(as_half2(w[p]), as_half2(xr[p]), a0, false);
+                if (u + 1 < R) {
+                    w[p] = *reinterpret_cast<const u32*>(tb + pair_offset_of(c[u + 1], p));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
+            acc[u] = a0 + a1;
         }
         __builtin_amdgcn_sched_barrier(0);
     }
